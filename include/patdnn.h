@@ -1,0 +1,185 @@
+/*
+ * patdnn.h - C ABI of the MI355X (gfx950) pattern-sparse 3x3 convolution library.
+ *
+ * The library runs the inference hot path of PatDNN (ASPLOS'20): 3x3 CONV layers
+ * (paper section 2.1) whose weights obey the two constraints of section 4.2 - every
+ * surviving kernel keeps only the four positions of one pattern out of a small
+ * pattern set (section 3.1, 4.1), and whole kernels are removed (connectivity
+ * pruning).  `patdnn_encode` is the offline stage of section 5 (filter-kernel
+ * reorder, compact weight storage); `patdnn_conv2d` is the generated layer code.
+ *
+ * Conventions
+ *   - All functions are extern "C", never throw, and return a patdnn_status_t
+ *     (PATDNN_OK == 0).  `patdnn_last_error()` returns a thread-local text for the
+ *     last failure on the calling thread.
+ *   - HOST pointers are ordinary process memory; DEVICE pointers are HIP device
+ *     memory on the device that was current when the handle was encoded.
+ *   - Tensors are dense, contiguous, fp32.  Weights are OIHW, activations NCHW.
+ *   - The operation is cross-correlation (no kernel flip), zero padding:
+ *       out[n][co][oh][ow] = act(bias[co] + sum_{ci,kh,kw} Wm[co][ci][kh][kw]
+ *                                 * in[n][ci][oh*stride+kh-pad][ow*stride+kw-pad])
+ *     where Wm is W with every position outside the kernel's pattern, and every
+ *     removed kernel, set to zero.  H_out = floor((H + 2*pad - 3)/stride) + 1.
+ *   - Pattern masks: bit (3*kh + kw) set = position kept.  The four stored weights
+ *     of a kernel are in ascending bit order.
+ */
+#ifndef PATDNN_H
+#define PATDNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct patdnn_layer* patdnn_handle_t;
+
+typedef enum {
+    PATDNN_OK = 0,
+    PATDNN_EINVAL = 1,        /* null pointer, non-positive size, bad stride/pad/groups */
+    PATDNN_EPATTERN = 2,      /* pattern id out of range, mask popcount != 4, or (STRICT) a
+                                 non-zero weight outside its pattern / in a removed kernel */
+    PATDNN_ENOMEM = 3,        /* host allocation failed */
+    PATDNN_EHIP = 4,          /* a HIP runtime call failed (no device, launch error, ...) */
+    PATDNN_EUNSUPPORTED = 5   /* valid request that this build does not implement */
+} patdnn_status_t;
+
+/* patdnn_layer_desc_t.flags */
+#define PATDNN_DENSE      0x1u  /* no pruning: ids and kernel_mask ignored, all nine taps kept
+                                   (the paper leaves the first layer alone, section 4.2) */
+#define PATDNN_STRICT     0x2u  /* reject weights that are non-zero where the constraints of
+                                   section 4.2 require zero, instead of ignoring them */
+#define PATDNN_HOST_ONLY  0x4u  /* build the layout in host memory only (no device needed);
+                                   decode/stats/export work, conv2d/tune return PATDNN_EHIP */
+
+typedef struct {
+    int32_t c_out;                 /* number of filters */
+    int32_t c_in;                  /* input channels */
+    int32_t groups;                /* 1, or c_in (== c_out): depthwise, one kernel per filter */
+    int32_t stride;                /* 1 or 2 */
+    int32_t pad;                   /* 0 or 1 */
+    int32_t num_patterns;          /* 1..255 (ignored with PATDNN_DENSE) */
+    const uint16_t* pattern_masks; /* HOST [num_patterns]; each must have exactly 4 bits set
+                                      below bit 9 and keep the centre (bit 4), section 4.1 */
+    uint32_t flags;
+} patdnn_layer_desc_t;
+
+/*
+ * Offline stage (paper section 5.2 filter-kernel reorder, 5.3 compact storage).
+ * Reads the three host arrays, builds the reordered compressed layout and uploads
+ * it; the caller may free its arrays as soon as the call returns.
+ *   dense_weights  HOST [c_out][c_in/groups][3][3]
+ *   pattern_ids    HOST [c_out][c_in/groups], each < num_patterns; not read where the
+ *                  kernel is removed; NULL allowed with PATDNN_DENSE
+ *   kernel_mask    HOST [c_out][c_in/groups], non-zero = kept; NULL = all kept
+ *   out            receives the handle; set to NULL on failure
+ * Weights outside a kernel's pattern and weights of removed kernels are ignored
+ * (or rejected with PATDNN_STRICT).  A filter with no kept kernel is legal.
+ */
+patdnn_status_t patdnn_encode(const patdnn_layer_desc_t* desc, const float* dense_weights,
+                              const uint8_t* pattern_ids, const uint8_t* kernel_mask,
+                              patdnn_handle_t* out);
+
+/*
+ * The layer itself (section 2.1 CONV + ReLU; executed from the reordered layout as
+ * in section 5.2-5.4).  Asynchronous on `stream`; allocates nothing, never
+ * synchronises.
+ *   input   DEVICE [n][c_in][h_in][w_in]
+ *   bias    DEVICE [c_out], or NULL for no bias
+ *   output  DEVICE [n][c_out][h_out][w_out]; must not overlap input
+ *   stream  a hipStream_t (NULL = the default stream)
+ * n == 0 is a no-op.  Tensors are limited to 2^31-1 elements per image
+ * (c*h*w) and the whole call to what 64-bit offsets address.
+ */
+patdnn_status_t patdnn_conv2d(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
+                              int32_t w_in, const float* bias, float* output,
+                              int32_t fuse_relu, void* stream);
+
+/* out_nchw = {n, c_out, h_out, w_out}; PATDNN_EINVAL if the output would be empty. */
+patdnn_status_t patdnn_output_shape(patdnn_handle_t h, int32_t n, int32_t h_in, int32_t w_in,
+                                    int32_t out_nchw[4]);
+
+/*
+ * Inverse of encode, read back from the stored (device-resident) layout: the exact
+ * fp32 bits at pattern positions of kept kernels and +0.0 elsewhere, the caller's
+ * pattern id for every kept kernel (0 for removed ones and for dense layers), and
+ * the 0/1 kernel mask.  Any output pointer may be NULL.  All HOST.
+ */
+patdnn_status_t patdnn_decode(patdnn_handle_t h, float* dense_weights, uint8_t* pattern_ids,
+                              uint8_t* kernel_mask);
+
+/*
+ * The five arrays of the paper's FKW format (section 5.3) as stored for this
+ * layer, copied to HOST buffers (any may be NULL to skip):
+ *   offset  [c_out+1]  cumulative kept kernels per stored filter
+ *   reorder [c_out]    original output channel of each stored filter
+ *   index   [kept]     input channel of each stored kernel
+ *   stride  [c_out][num_patterns+1]  cumulative kernels per pattern, per filter
+ *   weight  [kept][taps]  taps = 4 (9 for a dense layer)
+ * Sizes come from patdnn_layout_stats.
+ */
+patdnn_status_t patdnn_export_fkw(patdnn_handle_t h, int32_t* offset, int32_t* reorder,
+                                  int32_t* index, int32_t* stride, float* weight);
+
+typedef struct {
+    int64_t kept_kernels;      /* kernels that survived connectivity pruning */
+    int32_t taps;              /* stored weights per kernel: 4, or 9 for a dense layer */
+    int32_t num_patterns;      /* patterns of the layer (1 for dense) */
+    int64_t fkw_weight_bytes;  /* weight array */
+    int64_t fkw_index_bytes;   /* offset + reorder + index + stride arrays */
+    int64_t tiled_bytes;       /* device bytes of the per-filter-group layouts the tiled kernels read */
+    int32_t min_filter_length, max_filter_length;
+    int32_t distinct_filter_lengths;
+    int32_t filter_groups;     /* groups of the default tiled layout (0 if none) */
+    int32_t group_size;        /* filters per group of that layout */
+    int64_t max_group_kernels, min_group_kernels;   /* kept kernels in the fullest / emptiest group */
+} patdnn_stats_t;
+
+patdnn_status_t patdnn_layout_stats(patdnn_handle_t h, patdnn_stats_t* out);
+
+/*
+ * Launch configuration of one layer.  `variant` selects the kernel:
+ *   0  PATDNN_VARIANT_FKW   filter-major walk of the FKW arrays, one lane per output
+ *                           pixel (handles every shape; the reorder-only code of
+ *                           section 5.2)
+ *   >0 tiled variants       LDS-staged input tiles, register patches, filter groups
+ *                           (section 5.4 load-redundancy elimination); see
+ *                           patdnn_variant_name
+ * `ck` = input channels staged per LDS pass, `waves` = wavefronts (filter groups)
+ * per workgroup; 0 lets the library choose.
+ */
+typedef struct {
+    int32_t variant;
+    int32_t ck;
+    int32_t waves;
+    int32_t reserved;
+} patdnn_config_t;
+
+#define PATDNN_VARIANT_FKW 0
+
+int32_t         patdnn_num_variants(void);
+const char*     patdnn_variant_name(int32_t variant);   /* NULL if out of range */
+/* PATDNN_EUNSUPPORTED if the variant cannot run this layer (stride, depthwise, ...). */
+patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg);
+patdnn_status_t patdnn_get_config(patdnn_handle_t h, patdnn_config_t* cfg);
+
+/*
+ * Parameter auto-tuning (section 5.5), reduced to an exhaustive timed search over
+ * the variants and launch parameters that can run this layer at this input size.
+ * Runs every candidate on the caller's buffers (output is overwritten with a valid
+ * result of the last candidate), synchronises the stream, keeps the fastest in the
+ * handle and reports it.  `best_us` may be NULL.
+ */
+patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
+                            int32_t w_in, const float* bias, float* output, void* stream,
+                            float* best_us);
+
+void        patdnn_destroy(patdnn_handle_t h);          /* NULL is a no-op */
+const char* patdnn_status_string(patdnn_status_t s);
+const char* patdnn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PATDNN_H */

@@ -1,0 +1,236 @@
+// Offline stage: validation, filter-kernel reorder (paper section 5.2), FKW compact
+// storage (section 5.3) and the channel-major filter-group layout of the tiled
+// kernels.  Pure host code; no HIP calls.
+#include "layout.hpp"
+
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+
+namespace patdnn {
+
+int universe_index(uint16_t mask)
+{
+    for (int i = 0; i < kUniverse; ++i)
+        if (universe_mask(i) == mask) return i;
+    return -1;
+}
+
+static int popcount16(unsigned v)
+{
+    int c = 0;
+    for (; v; v &= v - 1) ++c;
+    return c;
+}
+
+patdnn_status_t build_fkw(const patdnn_layer_desc_t& d, const float* w, const uint8_t* ids,
+                          const uint8_t* mask, LayerHost& L, std::string& err)
+{
+    if (!w) { err = "dense_weights is NULL"; return PATDNN_EINVAL; }
+    if (d.c_out <= 0 || d.c_in <= 0) { err = "c_out and c_in must be positive"; return PATDNN_EINVAL; }
+    if (d.stride != 1 && d.stride != 2) { err = "stride must be 1 or 2"; return PATDNN_EINVAL; }
+    if (d.pad != 0 && d.pad != 1) { err = "pad must be 0 or 1"; return PATDNN_EINVAL; }
+    const bool depthwise = d.groups != 1;
+    if (d.groups != 1 && !(d.groups == d.c_in && d.c_in == d.c_out)) {
+        err = "groups must be 1, or equal to c_in == c_out (depthwise)";
+        return PATDNN_EINVAL;
+    }
+    const bool dense = (d.flags & PATDNN_DENSE) != 0;
+    const int kpf = depthwise ? 1 : d.c_in;          // kernels per filter
+    const int P = dense ? 1 : d.num_patterns;
+
+    L.desc = d;
+    L.desc.pattern_masks = nullptr;
+    L.depthwise = depthwise;
+    L.dense = dense;
+    L.all_in_universe = true;
+    Fkw& f = L.fkw;
+    f = Fkw();
+    f.taps = dense ? 9 : 4;
+    f.num_patterns = P;
+
+    if (dense) {
+        f.masks.assign(1, 0x1FF);
+        L.universe_of_pattern.assign(1, 255);
+    } else {
+        if (d.num_patterns < 1 || d.num_patterns > 255) {
+            err = "num_patterns must be in 1..255";
+            return PATDNN_EINVAL;
+        }
+        if (!d.pattern_masks || !ids) { err = "pattern_masks / pattern_ids is NULL"; return PATDNN_EINVAL; }
+        f.masks.assign(d.pattern_masks, d.pattern_masks + P);
+        L.universe_of_pattern.resize(P);
+        for (int p = 0; p < P; ++p) {
+            if (f.masks[p] >= 512 || popcount16(f.masks[p]) != 4) {
+                err = "pattern mask " + std::to_string(p) + " does not keep exactly 4 of the 9 positions";
+                return PATDNN_EPATTERN;
+            }
+            const int u = universe_index(f.masks[p]);
+            L.universe_of_pattern[p] = (uint8_t)(u < 0 ? 255 : u);
+            if (u < 0) L.all_in_universe = false;
+        }
+    }
+
+    auto kept_at = [&](int co, int k) -> bool {
+        return dense || !mask || mask[(size_t)co * kpf + k] != 0;
+    };
+
+    // validation of ids (kept kernels only) and, if asked, of the zero structure
+    for (int co = 0; co < d.c_out; ++co)
+        for (int k = 0; k < kpf; ++k) {
+            const size_t kid = (size_t)co * kpf + k;
+            const bool kept = kept_at(co, k);
+            if (kept && !dense && ids[kid] >= P) {
+                err = "pattern id out of range at filter " + std::to_string(co) + ", kernel " + std::to_string(k);
+                return PATDNN_EPATTERN;
+            }
+            if (d.flags & PATDNN_STRICT) {
+                const unsigned m = !kept ? 0u : f.masks[dense ? 0 : ids[kid]];
+                for (int p = 0; p < 9; ++p)
+                    if (!((m >> p) & 1u) && w[kid * 9 + p] != 0.0f) {
+                        err = "non-zero weight outside the pattern at filter " + std::to_string(co) +
+                              ", kernel " + std::to_string(k);
+                        return PATDNN_EPATTERN;
+                    }
+            }
+        }
+
+    // ---- filter reorder: by length, then by per-pattern kernel counts, then by index
+    std::vector<int32_t> length(d.c_out, 0);
+    std::vector<int32_t> counts((size_t)d.c_out * P, 0);
+    for (int co = 0; co < d.c_out; ++co)
+        for (int k = 0; k < kpf; ++k)
+            if (kept_at(co, k)) {
+                ++length[co];
+                ++counts[(size_t)co * P + (dense ? 0 : ids[(size_t)co * kpf + k])];
+            }
+    std::vector<int32_t> order(d.c_out);
+    std::iota(order.begin(), order.end(), 0);
+    std::sort(order.begin(), order.end(), [&](int a, int b) {
+        if (length[a] != length[b]) return length[a] < length[b];
+        const int32_t* ca = &counts[(size_t)a * P];
+        const int32_t* cb = &counts[(size_t)b * P];
+        for (int p = 0; p < P; ++p)
+            if (ca[p] != cb[p]) return ca[p] < cb[p];
+        return a < b;
+    });
+
+    // ---- kernel reorder + the five arrays
+    int64_t kept_total = 0;
+    for (int co = 0; co < d.c_out; ++co) kept_total += length[co];
+    if (kept_total > INT32_MAX / 16) { err = "layer too large"; return PATDNN_EUNSUPPORTED; }
+    L.kept = kept_total;
+    f.offset.assign(d.c_out + 1, 0);
+    f.reorder.assign(order.begin(), order.end());
+    f.stride.assign((size_t)d.c_out * (P + 1), 0);
+    f.index.resize(kept_total);
+    f.weight.resize((size_t)kept_total * f.taps);
+    int32_t pos = 0;
+    for (int s = 0; s < d.c_out; ++s) {
+        const int co = order[s];
+        f.offset[s] = pos;
+        int32_t* st = &f.stride[(size_t)s * (P + 1)];
+        for (int p = 0; p < P; ++p) {
+            st[p] = pos - f.offset[s];
+            for (int k = 0; k < kpf; ++k) {          // ascending input channel inside a pattern
+                const size_t kid = (size_t)co * kpf + k;
+                if (!kept_at(co, k)) continue;
+                if (!dense && ids[kid] != p) continue;
+                f.index[pos] = depthwise ? co : k;
+                const unsigned m = f.masks[p];
+                float* dst = &f.weight[(size_t)pos * f.taps];
+                int t = 0;
+                for (int q = 0; q < 9; ++q)
+                    if ((m >> q) & 1u) dst[t++] = w[kid * 9 + q];
+                ++pos;
+            }
+        }
+        st[P] = pos - f.offset[s];
+    }
+    f.offset[d.c_out] = pos;
+    return PATDNN_OK;
+}
+
+void decode_fkw(const LayerHost& L, const Fkw& f, float* w, uint8_t* ids, uint8_t* mask)
+{
+    const int c_out = L.desc.c_out;
+    const int kpf = L.depthwise ? 1 : L.desc.c_in;
+    const int P = f.num_patterns;
+    const size_t nk = (size_t)c_out * kpf;
+    if (w) std::memset(w, 0, nk * 9 * sizeof(float));
+    if (ids) std::memset(ids, 0, nk);
+    if (mask) std::memset(mask, 0, nk);
+    for (int s = 0; s < c_out; ++s) {
+        const int co = f.reorder[s];
+        const int32_t* st = &f.stride[(size_t)s * (P + 1)];
+        for (int p = 0; p < P; ++p)
+            for (int32_t k = f.offset[s] + st[p]; k < f.offset[s] + st[p + 1]; ++k) {
+                const int kk = L.depthwise ? 0 : f.index[k];
+                const size_t kid = (size_t)co * kpf + kk;
+                if (mask) mask[kid] = 1;
+                if (ids) ids[kid] = L.dense ? 0 : (uint8_t)p;
+                if (w) {
+                    const unsigned m = f.masks[p];
+                    int t = 0;
+                    for (int q = 0; q < 9; ++q)
+                        if ((m >> q) & 1u) w[kid * 9 + q] = f.weight[(size_t)k * f.taps + t++];
+                }
+            }
+    }
+}
+
+void build_tiled(const LayerHost& L, int G, Tiled& T)
+{
+    const Fkw& f = L.fkw;
+    const int c_out = L.desc.c_out, c_in = L.desc.c_in, P = f.num_patterns;
+    T = Tiled();
+    T.G = G;
+    T.dense = L.dense;
+    T.num_groups = (c_out + G - 1) / G;
+    T.slot_channel.assign((size_t)T.num_groups * G, -1);
+
+    struct Entry { uint32_t chan, upat, slot; int32_t k; };
+    if (L.dense) T.w9.assign((size_t)T.num_groups * c_in * G * 9, 0.0f);
+    else T.chan_ptr.assign((size_t)T.num_groups * (c_in + 1), 0);
+
+    std::vector<Entry> ent;
+    for (int g = 0; g < T.num_groups; ++g) {
+        ent.clear();
+        for (int slot = 0; slot < G; ++slot) {
+            const int r = g * G + slot;               // rank among filters, longest first
+            if (r >= c_out) break;
+            const int s = c_out - 1 - r;              // FKW position (lengths ascend there)
+            T.slot_channel[(size_t)g * G + slot] = f.reorder[s];
+            const int32_t* st = &f.stride[(size_t)s * (P + 1)];
+            for (int p = 0; p < P; ++p)
+                for (int32_t k = f.offset[s] + st[p]; k < f.offset[s] + st[p + 1]; ++k) {
+                    if (L.dense) {
+                        float* dst = &T.w9[(((size_t)g * c_in + f.index[k]) * G + slot) * 9];
+                        std::memcpy(dst, &f.weight[(size_t)k * 9], 9 * sizeof(float));
+                    } else {
+                        ent.push_back({(uint32_t)f.index[k], L.universe_of_pattern[p], (uint32_t)slot, k});
+                    }
+                }
+        }
+        if (L.dense) continue;
+        std::sort(ent.begin(), ent.end(), [](const Entry& a, const Entry& b) {
+            if (a.chan != b.chan) return a.chan < b.chan;
+            if (a.upat != b.upat) return a.upat < b.upat;
+            return a.slot < b.slot;
+        });
+        uint32_t* cp = &T.chan_ptr[(size_t)g * (c_in + 1)];
+        const uint32_t base = (uint32_t)T.code.size();
+        size_t e = 0;
+        for (int c = 0; c <= c_in; ++c) {
+            while (e < ent.size() && (int)ent[e].chan < c) ++e;
+            cp[c] = base + (uint32_t)e;
+        }
+        for (const Entry& x : ent) {
+            T.code.push_back((x.chan << 16) | (x.slot * (uint32_t)kUniverse + x.upat));
+            const float* src = &f.weight[(size_t)x.k * 4];
+            T.w4.insert(T.w4.end(), src, src + 4);
+        }
+    }
+}
+
+}  // namespace patdnn

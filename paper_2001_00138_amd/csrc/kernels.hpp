@@ -1,0 +1,61 @@
+// Device-side views of an encoded layer and the launchers of each kernel family.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace patdnn {
+
+struct ConvShape {
+    int32_t n, c_in, c_out, h, w, ho, wo, stride, pad, relu;
+};
+
+// FKW arrays on the device (paper section 5.3).
+struct DevFkw {
+    const int32_t* offset = nullptr;
+    const int32_t* reorder = nullptr;
+    const int32_t* index = nullptr;
+    const int32_t* stride = nullptr;
+    const float* weight = nullptr;
+    const uint16_t* masks = nullptr;
+    int32_t num_patterns = 0;
+    int32_t taps = 4;
+};
+
+// Channel-major filter-group layout on the device.
+struct DevTiled {
+    int32_t G = 0;
+    int32_t num_groups = 0;
+    const int32_t* slot_channel = nullptr;
+    const uint32_t* chan_ptr = nullptr;
+    const uint32_t* code = nullptr;
+    const float* w4 = nullptr;
+    const float* w9 = nullptr;
+};
+
+// Filter-major walk of the FKW arrays, one lane per output pixel.
+hipError_t launch_fkw(const DevFkw& f, const ConvShape& s, const float* in, const float* bias,
+                      float* out, hipStream_t stream);
+
+// ---------------------------------------------------------------------------
+// Tiled kernels: compile-time geometry per variant, run-time launch parameters.
+// ---------------------------------------------------------------------------
+struct TiledVariant {
+    const char* name;
+    int32_t G;        // filters per group (one group per wavefront)
+    int32_t PR, PC;   // output patch per lane (rows x columns)
+    int32_t S;        // stride
+    int32_t TGX;      // lanes across a band; a wavefront covers 64/TGX bands
+    bool dense;       // nine taps, every kernel present
+    int32_t lds_floats_per_channel;   // LDS floats one staged channel takes
+    int32_t stage_elems;              // elements staged per channel (without bank padding)
+    int32_t max_slots;                // staging elements per thread the kernel can hold
+    hipError_t (*launch)(const DevTiled&, const ConvShape&, const float*, const float*, float*,
+                         int32_t ck, int32_t waves, hipStream_t);
+};
+
+int num_tiled_variants();
+const TiledVariant& tiled_variant(int i);
+
+}  // namespace patdnn

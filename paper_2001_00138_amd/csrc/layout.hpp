@@ -1,0 +1,94 @@
+// Host-side description of an encoded layer: the paper's FKW arrays (section 5.3)
+// plus the per-filter-group, channel-major layouts that the tiled kernels read.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/patdnn.h"
+
+namespace patdnn {
+
+// ---------------------------------------------------------------------------
+// The 56 four-entry patterns that keep the centre (section 4.1), numbered by the
+// lexicographic order of their three non-centre positions.  Tiled kernels carry one
+// straight-line body per entry of this table, so a layer may use any subset of it.
+// ---------------------------------------------------------------------------
+constexpr int kUniverse = 56;
+
+constexpr uint16_t universe_mask(int idx)
+{
+    const int others[8] = {0, 1, 2, 3, 5, 6, 7, 8};
+    int k = 0;
+    for (int a = 0; a < 8; ++a)
+        for (int b = a + 1; b < 8; ++b)
+            for (int c = b + 1; c < 8; ++c) {
+                if (k == idx)
+                    return (uint16_t)((1u << 4) | (1u << others[a]) | (1u << others[b]) |
+                                      (1u << others[c]));
+                ++k;
+            }
+    return 0;
+}
+
+int universe_index(uint16_t mask);   // -1 if the mask is not one of the 56
+
+// ---------------------------------------------------------------------------
+// FKW (section 5.3): filter-major, kernels of a filter ordered by pattern.
+// ---------------------------------------------------------------------------
+struct Fkw {
+    int32_t taps = 4;                 // weights per stored kernel (9 for a dense layer)
+    int32_t num_patterns = 0;         // P (1 for a dense layer)
+    std::vector<int32_t> offset;      // [c_out+1]
+    std::vector<int32_t> reorder;     // [c_out]   stored filter -> original output channel
+    std::vector<int32_t> index;       // [kept]    input channel
+    std::vector<int32_t> stride;      // [c_out][P+1]
+    std::vector<float> weight;        // [kept][taps]
+    std::vector<uint16_t> masks;      // [P] pattern masks (0x1FF for dense)
+};
+
+// ---------------------------------------------------------------------------
+// Tiled layout for one group size G.  Filters are taken G at a time from the FKR
+// order, longest first; inside a group the kept kernels are listed channel-major so
+// that one staged input window serves every kernel of the group on that channel
+// (filter-level load-redundancy elimination, section 5.4).
+// ---------------------------------------------------------------------------
+struct Tiled {
+    int32_t G = 0;
+    int32_t num_groups = 0;
+    bool dense = false;
+    std::vector<int32_t> slot_channel;   // [num_groups*G] original output channel, -1 = empty slot
+    // sparse layers
+    std::vector<uint32_t> chan_ptr;      // [num_groups][c_in+1] entry ranges per input channel
+    std::vector<uint32_t> code;          // [kept] (channel << 16) | (slot * 56 + universe index)
+    std::vector<float> w4;               // [kept][4]
+    // dense layers
+    std::vector<float> w9;               // [num_groups][c_in][G][9]
+    size_t bytes() const
+    {
+        return 4 * (slot_channel.size() + chan_ptr.size() + code.size() + w4.size() + w9.size());
+    }
+};
+
+struct LayerHost {
+    patdnn_layer_desc_t desc{};          // pattern_masks pointer is not kept; see fkw.masks
+    bool depthwise = false;
+    bool dense = false;
+    bool all_in_universe = true;         // every used mask is one of the 56
+    int64_t kept = 0;
+    Fkw fkw;
+    std::vector<uint8_t> universe_of_pattern;  // [P] universe index per pattern id (255 = none)
+};
+
+// Validation + FKR + FKW.  Returns PATDNN_OK or an error with `err` filled.
+patdnn_status_t build_fkw(const patdnn_layer_desc_t& d, const float* w, const uint8_t* ids,
+                          const uint8_t* mask, LayerHost& out, std::string& err);
+
+// Channel-major group layout derived from the FKW arrays.
+void build_tiled(const LayerHost& L, int G, Tiled& out);
+
+// Inverse of build_fkw from the five arrays (any output may be null).
+void decode_fkw(const LayerHost& L, const Fkw& f, float* w, uint8_t* ids, uint8_t* mask);
+
+}  // namespace patdnn

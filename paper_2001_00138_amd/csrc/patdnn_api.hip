@@ -1,0 +1,494 @@
+// C ABI of the library (see include/patdnn.h): handle management, upload of the
+// encoded layouts, variant selection, launch, decode, tuning.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.hpp"
+#include "layout.hpp"
+
+using namespace patdnn;
+
+namespace {
+
+thread_local std::string g_err;
+
+patdnn_status_t fail(patdnn_status_t s, const std::string& msg)
+{
+    g_err = msg;
+    return s;
+}
+
+patdnn_status_t hip_fail(hipError_t e, const char* what)
+{
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    return PATDNN_EHIP;
+}
+
+struct TiledOnDevice {
+    Tiled host;
+    DevTiled dev;
+};
+
+}  // namespace
+
+struct patdnn_layer {
+    LayerHost L;
+    bool on_device = false;
+    int device = -1;
+    DevFkw dfkw;
+    std::map<int, std::unique_ptr<TiledOnDevice>> tiled;   // by group size G
+    std::vector<void*> allocations;
+    patdnn_config_t cfg{-1, 0, 0, 0};                      // variant -1: choose per call
+
+    ~patdnn_layer()
+    {
+        for (void* p : allocations) (void)hipFree(p);
+    }
+};
+
+namespace {
+
+template <class T>
+hipError_t upload(patdnn_layer* h, const std::vector<T>& v, const T** out, size_t extra = 0)
+{
+    *out = nullptr;
+    const size_t bytes = (v.size() + extra) * sizeof(T);
+    if (bytes == 0) return hipSuccess;
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) return e;
+    h->allocations.push_back(p);
+    if (extra) {
+        e = hipMemset(p, 0, bytes);
+        if (e != hipSuccess) return e;
+    }
+    if (!v.empty()) {
+        e = hipMemcpy(p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return e;
+    }
+    *out = static_cast<const T*>(p);
+    return hipSuccess;
+}
+
+bool variant_fits_layer(const patdnn_layer* h, const TiledVariant& v)
+{
+    const LayerHost& L = h->L;
+    if (L.depthwise) return false;
+    if (v.dense != L.dense) return false;
+    if (v.S != L.desc.stride) return false;
+    if (!L.dense && !L.all_in_universe) return false;
+    if (L.desc.c_in > 65535) return false;
+    return true;
+}
+
+constexpr int kMaxLdsBytes = 64 * 1024;
+constexpr int kMaxWaves = 8;
+
+// Smallest / default launch parameters of a tiled variant for this layer; false if
+// the variant cannot run at all.
+bool resolve_tiled_params(const patdnn_layer* h, const TiledVariant& v, const ConvShape& s,
+                          int32_t& ck, int32_t& waves)
+{
+    const int num_groups = (h->L.desc.c_out + v.G - 1) / v.G;
+    const int min_waves = (v.stage_elems + 64 * v.max_slots - 1) / (64 * v.max_slots);
+    if (min_waves > kMaxWaves) return false;
+    if (waves <= 0) waves = std::max(min_waves, std::min(num_groups, 4));
+    if (waves < min_waves || waves > kMaxWaves) return false;
+    const int max_ck = kMaxLdsBytes / (4 * v.lds_floats_per_channel);
+    if (max_ck < 1) return false;
+    if (ck <= 0) ck = std::min(std::min(8, max_ck), s.c_in);
+    if (ck < 1 || ck > max_ck) return false;
+    // staging offsets are 32-bit, relative to the first image of a tile
+    const int nb = 64 / v.TGX;
+    const long long span = (long long)(nb + 1) * s.c_in * s.h * s.w;
+    if (span >= (1ll << 31)) return false;
+    return true;
+}
+
+patdnn_status_t ensure_tiled(patdnn_layer* h, int G, const DevTiled** out)
+{
+    auto it = h->tiled.find(G);
+    if (it == h->tiled.end()) {
+        std::unique_ptr<TiledOnDevice> t(new (std::nothrow) TiledOnDevice());
+        if (!t) return fail(PATDNN_ENOMEM, "out of host memory");
+        build_tiled(h->L, G, t->host);
+        t->dev.G = G;
+        t->dev.num_groups = t->host.num_groups;
+        if (h->on_device) {
+            hipError_t e;
+            if ((e = upload(h, t->host.slot_channel, &t->dev.slot_channel)) != hipSuccess ||
+                (e = upload(h, t->host.chan_ptr, &t->dev.chan_ptr)) != hipSuccess ||
+                // one dummy entry past the end: the kernel fetches one entry ahead
+                (e = upload(h, t->host.code, &t->dev.code, 1)) != hipSuccess ||
+                (e = upload(h, t->host.w4, &t->dev.w4, 4)) != hipSuccess ||
+                (e = upload(h, t->host.w9, &t->dev.w9)) != hipSuccess)
+                return hip_fail(e, "uploading the tiled layout");
+        }
+        it = h->tiled.emplace(G, std::move(t)).first;
+    }
+    if (out) *out = &it->second->dev;
+    return PATDNN_OK;
+}
+
+patdnn_status_t shape_of(const patdnn_layer* h, int32_t n, int32_t h_in, int32_t w_in, ConvShape& s)
+{
+    if (!h) return fail(PATDNN_EINVAL, "handle is NULL");
+    if (n < 0 || h_in <= 0 || w_in <= 0) return fail(PATDNN_EINVAL, "n must be >= 0 and h_in, w_in positive");
+    const auto& d = h->L.desc;
+    s.n = n; s.c_in = d.c_in; s.c_out = d.c_out; s.h = h_in; s.w = w_in;
+    s.stride = d.stride; s.pad = d.pad;
+    s.ho = (h_in + 2 * d.pad - 3) / d.stride + 1;
+    s.wo = (w_in + 2 * d.pad - 3) / d.stride + 1;
+    s.relu = 0;
+    if (h_in + 2 * d.pad < 3 || w_in + 2 * d.pad < 3 || s.ho <= 0 || s.wo <= 0)
+        return fail(PATDNN_EINVAL, "input smaller than the 3x3 kernel");
+    if ((long long)d.c_in * h_in * w_in > INT32_MAX || (long long)d.c_out * s.ho * s.wo > INT32_MAX)
+        return fail(PATDNN_EUNSUPPORTED, "more than 2^31-1 elements per image");
+    return PATDNN_OK;
+}
+
+// Launch with an explicit configuration (variant >= 0).
+patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const ConvShape& s,
+                           const float* in, const float* bias, float* out, hipStream_t stream)
+{
+    if (c.variant == PATDNN_VARIANT_FKW) {
+        hipError_t e = launch_fkw(h->dfkw, s, in, bias, out, stream);
+        return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching the FKW kernel");
+    }
+    const int vi = c.variant - 1;
+    if (vi < 0 || vi >= num_tiled_variants()) return fail(PATDNN_EINVAL, "no such variant");
+    const TiledVariant& v = tiled_variant(vi);
+    if (!variant_fits_layer(h, v)) return fail(PATDNN_EUNSUPPORTED, "variant cannot run this layer");
+    int32_t ck = c.ck, waves = c.waves;
+    if (!resolve_tiled_params(h, v, s, ck, waves))
+        return fail(PATDNN_EUNSUPPORTED, "launch parameters outside the variant's limits");
+    const DevTiled* t = nullptr;
+    patdnn_status_t st = ensure_tiled(h, v.G, &t);
+    if (st != PATDNN_OK) return st;
+    hipError_t e = v.launch(*t, s, in, bias, out, ck, waves, stream);
+    return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching a tiled kernel");
+}
+
+// The configuration used when the caller has not chosen or tuned one.
+patdnn_config_t default_config(patdnn_layer* h, const ConvShape& s)
+{
+    for (int vi = 0; vi < num_tiled_variants(); ++vi) {
+        const TiledVariant& v = tiled_variant(vi);
+        if (!variant_fits_layer(h, v)) continue;
+        int32_t ck = 0, waves = 0;
+        if (resolve_tiled_params(h, v, s, ck, waves)) return patdnn_config_t{vi + 1, ck, waves, 0};
+    }
+    return patdnn_config_t{PATDNN_VARIANT_FKW, 0, 0, 0};
+}
+
+}  // namespace
+
+extern "C" {
+
+patdnn_status_t patdnn_encode(const patdnn_layer_desc_t* desc, const float* dense_weights,
+                              const uint8_t* pattern_ids, const uint8_t* kernel_mask,
+                              patdnn_handle_t* out)
+{
+    if (out) *out = nullptr;
+    if (!desc || !out) return fail(PATDNN_EINVAL, "desc / out is NULL");
+    std::unique_ptr<patdnn_layer> h(new (std::nothrow) patdnn_layer());
+    if (!h) return fail(PATDNN_ENOMEM, "out of host memory");
+    std::string err;
+    patdnn_status_t st;
+    try {
+        st = build_fkw(*desc, dense_weights, pattern_ids, kernel_mask, h->L, err);
+    } catch (const std::bad_alloc&) {
+        return fail(PATDNN_ENOMEM, "out of host memory");
+    }
+    if (st != PATDNN_OK) return fail(st, err);
+
+    if (!(desc->flags & PATDNN_HOST_ONLY)) {
+        hipError_t e = hipGetDevice(&h->device);
+        if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+        const Fkw& f = h->L.fkw;
+        if ((e = upload(h.get(), f.offset, &h->dfkw.offset)) != hipSuccess ||
+            (e = upload(h.get(), f.reorder, &h->dfkw.reorder)) != hipSuccess ||
+            (e = upload(h.get(), f.index, &h->dfkw.index)) != hipSuccess ||
+            (e = upload(h.get(), f.stride, &h->dfkw.stride)) != hipSuccess ||
+            (e = upload(h.get(), f.weight, &h->dfkw.weight)) != hipSuccess ||
+            (e = upload(h.get(), f.masks, &h->dfkw.masks)) != hipSuccess)
+            return hip_fail(e, "uploading the FKW arrays");
+        h->dfkw.num_patterns = f.num_patterns;
+        h->dfkw.taps = f.taps;
+        h->on_device = true;
+    }
+    // build (and upload) the group layouts of every tiled variant that can run the layer
+    try {
+        for (int vi = 0; vi < num_tiled_variants(); ++vi)
+            if (variant_fits_layer(h.get(), tiled_variant(vi))) {
+                st = ensure_tiled(h.get(), tiled_variant(vi).G, nullptr);
+                if (st != PATDNN_OK) return st;
+            }
+    } catch (const std::bad_alloc&) {
+        return fail(PATDNN_ENOMEM, "out of host memory");
+    }
+    *out = h.release();
+    return PATDNN_OK;
+}
+
+patdnn_status_t patdnn_output_shape(patdnn_handle_t h, int32_t n, int32_t h_in, int32_t w_in,
+                                    int32_t out_nchw[4])
+{
+    ConvShape s{};
+    patdnn_status_t st = shape_of(h, n, h_in, w_in, s);
+    if (st != PATDNN_OK) return st;
+    if (!out_nchw) return fail(PATDNN_EINVAL, "out_nchw is NULL");
+    out_nchw[0] = n; out_nchw[1] = s.c_out; out_nchw[2] = s.ho; out_nchw[3] = s.wo;
+    return PATDNN_OK;
+}
+
+patdnn_status_t patdnn_conv2d(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
+                              int32_t w_in, const float* bias, float* output, int32_t fuse_relu,
+                              void* stream)
+{
+    ConvShape s{};
+    patdnn_status_t st = shape_of(h, n, h_in, w_in, s);
+    if (st != PATDNN_OK) return st;
+    if (!h->on_device) return fail(PATDNN_EHIP, "handle was encoded with PATDNN_HOST_ONLY");
+    if (n == 0) return PATDNN_OK;
+    if (!input || !output) return fail(PATDNN_EINVAL, "input / output is NULL");
+    s.relu = fuse_relu ? 1 : 0;
+    patdnn_config_t c = h->cfg;
+    if (c.variant < 0) c = default_config(h, s);
+    st = run_config(h, c, s, input, bias, output, static_cast<hipStream_t>(stream));
+    if (st == PATDNN_EUNSUPPORTED && h->cfg.variant > 0) {
+        // a configuration chosen for another input size may not fit this one
+        c = default_config(h, s);
+        st = run_config(h, c, s, input, bias, output, static_cast<hipStream_t>(stream));
+    }
+    return st;
+}
+
+patdnn_status_t patdnn_decode(patdnn_handle_t h, float* dense_weights, uint8_t* pattern_ids,
+                              uint8_t* kernel_mask)
+{
+    if (!h) return fail(PATDNN_EINVAL, "handle is NULL");
+    try {
+        if (!h->on_device) {
+            decode_fkw(h->L, h->L.fkw, dense_weights, pattern_ids, kernel_mask);
+            return PATDNN_OK;
+        }
+        // read the five arrays back from device memory and invert them
+        Fkw f;
+        const Fkw& ref = h->L.fkw;
+        f.taps = ref.taps;
+        f.num_patterns = ref.num_patterns;
+        f.offset.resize(ref.offset.size());
+        f.reorder.resize(ref.reorder.size());
+        f.index.resize(ref.index.size());
+        f.stride.resize(ref.stride.size());
+        f.weight.resize(ref.weight.size());
+        f.masks.resize(ref.masks.size());
+        auto back = [](void* dst, const void* src, size_t bytes) -> hipError_t {
+            return bytes ? hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost) : hipSuccess;
+        };
+        hipError_t e;
+        if ((e = back(f.offset.data(), h->dfkw.offset, f.offset.size() * 4)) != hipSuccess ||
+            (e = back(f.reorder.data(), h->dfkw.reorder, f.reorder.size() * 4)) != hipSuccess ||
+            (e = back(f.index.data(), h->dfkw.index, f.index.size() * 4)) != hipSuccess ||
+            (e = back(f.stride.data(), h->dfkw.stride, f.stride.size() * 4)) != hipSuccess ||
+            (e = back(f.weight.data(), h->dfkw.weight, f.weight.size() * 4)) != hipSuccess ||
+            (e = back(f.masks.data(), h->dfkw.masks, f.masks.size() * 2)) != hipSuccess)
+            return hip_fail(e, "reading the FKW arrays back");
+        decode_fkw(h->L, f, dense_weights, pattern_ids, kernel_mask);
+    } catch (const std::bad_alloc&) {
+        return fail(PATDNN_ENOMEM, "out of host memory");
+    }
+    return PATDNN_OK;
+}
+
+patdnn_status_t patdnn_export_fkw(patdnn_handle_t h, int32_t* offset, int32_t* reorder,
+                                  int32_t* index, int32_t* stride, float* weight)
+{
+    if (!h) return fail(PATDNN_EINVAL, "handle is NULL");
+    const Fkw& f = h->L.fkw;
+    auto get = [&](void* dst, const void* dev, const void* host, size_t bytes) -> hipError_t {
+        if (!dst || !bytes) return hipSuccess;
+        if (h->on_device) return hipMemcpy(dst, dev, bytes, hipMemcpyDeviceToHost);
+        std::memcpy(dst, host, bytes);
+        return hipSuccess;
+    };
+    hipError_t e;
+    if ((e = get(offset, h->dfkw.offset, f.offset.data(), f.offset.size() * 4)) != hipSuccess ||
+        (e = get(reorder, h->dfkw.reorder, f.reorder.data(), f.reorder.size() * 4)) != hipSuccess ||
+        (e = get(index, h->dfkw.index, f.index.data(), f.index.size() * 4)) != hipSuccess ||
+        (e = get(stride, h->dfkw.stride, f.stride.data(), f.stride.size() * 4)) != hipSuccess ||
+        (e = get(weight, h->dfkw.weight, f.weight.data(), f.weight.size() * 4)) != hipSuccess)
+        return hip_fail(e, "reading the FKW arrays back");
+    return PATDNN_OK;
+}
+
+patdnn_status_t patdnn_layout_stats(patdnn_handle_t h, patdnn_stats_t* out)
+{
+    if (!h || !out) return fail(PATDNN_EINVAL, "handle / out is NULL");
+    const Fkw& f = h->L.fkw;
+    std::memset(out, 0, sizeof(*out));
+    out->kept_kernels = h->L.kept;
+    out->taps = f.taps;
+    out->num_patterns = f.num_patterns;
+    out->fkw_weight_bytes = (int64_t)f.weight.size() * 4;
+    out->fkw_index_bytes = 4 * (int64_t)(f.offset.size() + f.reorder.size() + f.index.size() + f.stride.size());
+    std::vector<int32_t> len;
+    for (size_t s = 0; s + 1 < f.offset.size(); ++s) len.push_back(f.offset[s + 1] - f.offset[s]);
+    if (!len.empty()) {
+        out->min_filter_length = *std::min_element(len.begin(), len.end());
+        out->max_filter_length = *std::max_element(len.begin(), len.end());
+        std::sort(len.begin(), len.end());
+        out->distinct_filter_lengths = (int32_t)(std::unique(len.begin(), len.end()) - len.begin());
+    }
+    for (const auto& kv : h->tiled) out->tiled_bytes += (int64_t)kv.second->host.bytes();
+    if (!h->tiled.empty()) {
+        const Tiled& t = h->tiled.begin()->second->host;
+        out->filter_groups = t.num_groups;
+        out->group_size = t.G;
+        if (!t.dense && t.num_groups > 0) {
+            int64_t mx = 0, mn = INT64_MAX;
+            const int c_in = h->L.desc.c_in;
+            for (int g = 0; g < t.num_groups; ++g) {
+                const int64_t k = (int64_t)t.chan_ptr[(size_t)g * (c_in + 1) + c_in] -
+                                  (int64_t)t.chan_ptr[(size_t)g * (c_in + 1)];
+                mx = std::max(mx, k);
+                mn = std::min(mn, k);
+            }
+            out->max_group_kernels = mx;
+            out->min_group_kernels = mn;
+        }
+    }
+    return PATDNN_OK;
+}
+
+int32_t patdnn_num_variants(void) { return 1 + num_tiled_variants(); }
+
+const char* patdnn_variant_name(int32_t variant)
+{
+    if (variant == PATDNN_VARIANT_FKW) return "fkw";
+    if (variant < 0 || variant > num_tiled_variants()) return nullptr;
+    return tiled_variant(variant - 1).name;
+}
+
+patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
+{
+    if (!h || !cfg) return fail(PATDNN_EINVAL, "handle / cfg is NULL");
+    if (cfg->variant < 0) {               // back to automatic choice
+        h->cfg = patdnn_config_t{-1, 0, 0, 0};
+        return PATDNN_OK;
+    }
+    if (cfg->variant > num_tiled_variants()) return fail(PATDNN_EINVAL, "no such variant");
+    if (cfg->variant > 0) {
+        const TiledVariant& v = tiled_variant(cfg->variant - 1);
+        if (!variant_fits_layer(h, v)) return fail(PATDNN_EUNSUPPORTED, "variant cannot run this layer");
+        if (cfg->ck < 0 || cfg->waves < 0 || cfg->waves > kMaxWaves)
+            return fail(PATDNN_EINVAL, "ck / waves out of range");
+        const int min_waves = (v.stage_elems + 64 * v.max_slots - 1) / (64 * v.max_slots);
+        if (cfg->waves && cfg->waves < min_waves)
+            return fail(PATDNN_EUNSUPPORTED, "too few wavefronts to stage a tile");
+        if (cfg->ck && cfg->ck * 4 * v.lds_floats_per_channel > kMaxLdsBytes)
+            return fail(PATDNN_EUNSUPPORTED, "ck exceeds the LDS budget");
+    }
+    h->cfg = *cfg;
+    h->cfg.reserved = 0;
+    return PATDNN_OK;
+}
+
+patdnn_status_t patdnn_get_config(patdnn_handle_t h, patdnn_config_t* cfg)
+{
+    if (!h || !cfg) return fail(PATDNN_EINVAL, "handle / cfg is NULL");
+    *cfg = h->cfg;
+    return PATDNN_OK;
+}
+
+patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
+                            int32_t w_in, const float* bias, float* output, void* stream_,
+                            float* best_us)
+{
+    ConvShape s{};
+    patdnn_status_t st = shape_of(h, n, h_in, w_in, s);
+    if (st != PATDNN_OK) return st;
+    if (!h->on_device) return fail(PATDNN_EHIP, "handle was encoded with PATDNN_HOST_ONLY");
+    if (n == 0 || !input || !output) return fail(PATDNN_EINVAL, "tuning needs n > 0 and real buffers");
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+
+    std::vector<patdnn_config_t> cands;
+    const int ck_opts[] = {4, 8, 16, 32};
+    const int wave_opts[] = {1, 2, 4, 8};
+    for (int vi = 0; vi < num_tiled_variants(); ++vi) {
+        const TiledVariant& v = tiled_variant(vi);
+        if (!variant_fits_layer(h, v)) continue;
+        const int groups = (s.c_out + v.G - 1) / v.G;
+        for (int ck : ck_opts)
+            for (int waves : wave_opts) {
+                int32_t ck2 = std::min(ck, s.c_in), w2 = waves;
+                if (w2 > 1 && w2 / 2 >= groups) continue;      // mostly idle wavefronts
+                if (!resolve_tiled_params(h, v, s, ck2, w2)) continue;
+                patdnn_config_t c{vi + 1, ck2, w2, 0};
+                bool dup = false;
+                for (const auto& o : cands) dup |= (o.variant == c.variant && o.ck == c.ck && o.waves == c.waves);
+                if (!dup) cands.push_back(c);
+            }
+    }
+    cands.push_back(patdnn_config_t{PATDNN_VARIANT_FKW, 0, 0, 0});
+
+    hipEvent_t e0, e1;
+    hipError_t e;
+    if ((e = hipEventCreate(&e0)) != hipSuccess) return hip_fail(e, "hipEventCreate");
+    if ((e = hipEventCreate(&e1)) != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e, "hipEventCreate"); }
+    float best = -1.0f;
+    patdnn_config_t best_cfg = cands.back();
+    patdnn_status_t result = PATDNN_OK;
+    for (const auto& c : cands) {
+        const int reps = 3;
+        st = run_config(h, c, s, input, bias, output, stream);           // warm-up
+        if (st != PATDNN_OK) { result = st; break; }
+        (void)hipEventRecord(e0, stream);
+        for (int r = 0; r < reps && st == PATDNN_OK; ++r) st = run_config(h, c, s, input, bias, output, stream);
+        (void)hipEventRecord(e1, stream);
+        if (st != PATDNN_OK) { result = st; break; }
+        if ((e = hipEventSynchronize(e1)) != hipSuccess) { result = hip_fail(e, "hipEventSynchronize"); break; }
+        float ms = 0.0f;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        ms /= reps;
+        if (best < 0.0f || ms < best) { best = ms; best_cfg = c; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (result != PATDNN_OK) return result;
+    // leave a valid result of the chosen configuration in `output`
+    st = run_config(h, best_cfg, s, input, bias, output, stream);
+    if (st != PATDNN_OK) return st;
+    if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    h->cfg = best_cfg;
+    if (best_us) *best_us = best * 1000.0f;
+    return PATDNN_OK;
+}
+
+void patdnn_destroy(patdnn_handle_t h) { delete h; }
+
+const char* patdnn_status_string(patdnn_status_t s)
+{
+    switch (s) {
+        case PATDNN_OK: return "ok";
+        case PATDNN_EINVAL: return "invalid argument";
+        case PATDNN_EPATTERN: return "pattern constraint violated";
+        case PATDNN_ENOMEM: return "out of host memory";
+        case PATDNN_EHIP: return "HIP runtime error";
+        case PATDNN_EUNSUPPORTED: return "unsupported";
+    }
+    return "unknown status";
+}
+
+const char* patdnn_last_error(void) { return g_err.c_str(); }
+
+}  // extern "C"

@@ -1,0 +1,193 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, and its offline stage (filter-kernel reorder + FKW
+storage, paper section 5.2 / 5.3) round-trips exactly.  Handles are encoded with
+PATDNN_HOST_ONLY, so no HIP call is made."""
+
+import os
+import re
+
+import numpy as np
+import pytest
+
+from conftest import ROOT, read_golden_kv
+from paper_2001_00138_amd import binding as B
+from paper_2001_00138_amd import workloads as wl
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2001_00138_amd import buildlib
+        buildlib.build()
+
+
+def _header_functions():
+    text = open(os.path.join(ROOT, "include", "patdnn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(patdnn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _header_functions()
+    assert len(names) >= 12
+    L = B.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in patdnn.h but not exported"
+    assert sorted(B.EXPORTS) == names
+    assert B.patdnn_num_variants() >= 2
+    assert B.patdnn_variant_name(0) == "fkw"
+    assert B.patdnn_variant_name(B.patdnn_num_variants()) is None
+
+
+def _host_layer(layer, **kw):
+    return B.Layer.from_workload(layer, host_only=True, **kw)
+
+
+@pytest.mark.parametrize("config,layer", [(1, 0), (2, 0), (2, 1), (2, 7), (3, 3), (4, 1), (4, 16)])
+def test_encode_decode_roundtrip(oracle, config, layer):
+    d = wl.gen_layer(config, layer, with_input=False)
+    spec = d["spec"]
+    L = _host_layer(d)
+    w, ids, km = L.decode()
+    want_w = oracle.masked_weights(d["weights"], d["pattern_ids"], d["kernel_mask"],
+                                   d["pattern_masks"], dense=spec.dense)
+    assert w.view(np.uint32).tolist() == want_w.view(np.uint32).tolist()   # exact bits
+    if spec.dense:
+        assert km.all() and not ids.any()
+    else:
+        np.testing.assert_array_equal(km, d["kernel_mask"])
+        np.testing.assert_array_equal(ids, d["pattern_ids"] * d["kernel_mask"])
+    st = L.stats()
+    assert st["kept_kernels"] == int(km.sum()) == wl.kept_kernel_count(spec)
+    assert st["taps"] == (9 if spec.dense else 4)
+    assert st["fkw_weight_bytes"] == 4 * st["taps"] * st["kept_kernels"]
+    L.close()
+
+
+def test_fkw_arrays_follow_the_paper(oracle):
+    """The exported arrays obey section 5.3, and coincide with the oracle's own
+    construction (same stated reading of the tie-breaks)."""
+    from oracle import fkw
+    d = wl.gen_layer(3, 0, with_input=False)            # 64 -> 64
+    L = _host_layer(d)
+    f = L.export_fkw()
+    ref = fkw.build_fkw(d["weights"], d["pattern_ids"], d["kernel_mask"], d["pattern_masks"])
+    c_out = d["spec"].c_out
+    lengths = np.diff(f["offset"])
+    assert (np.diff(lengths) >= 0).all()                        # grouped by length
+    assert sorted(f["reorder"]) == list(range(c_out))           # a permutation
+    for s, co in enumerate(f["reorder"]):
+        ch = f["index"][f["offset"][s]:f["offset"][s + 1]]
+        assert sorted(ch) == list(np.flatnonzero(d["kernel_mask"][co]))
+        assert (np.diff(d["pattern_ids"][co, ch].astype(int)) >= 0).all()   # grouped by pattern
+        assert f["stride"][s, 0] == 0 and f["stride"][s, -1] == len(ch)
+    np.testing.assert_array_equal(f["offset"], ref.offset)
+    np.testing.assert_array_equal(f["reorder"], ref.reorder)
+    np.testing.assert_array_equal(f["index"], ref.index)
+    np.testing.assert_array_equal(f["stride"], ref.stride)
+    assert f["weight"].view(np.uint32).tolist() == ref.weight.view(np.uint32).tolist()
+    # the exported arrays, walked as the paper describes, compute the layer
+    x = wl.gen_input(d["spec"], 3, 0, 1)[:, :, :12, :12]
+    got = fkw.fkw_conv2d(fkw.FKW(f["offset"], f["reorder"], f["index"], f["stride"], f["weight"],
+                                 d["pattern_masks"]), x, d["bias"], relu=True)
+    want = oracle.conv2d(d["weights"], d["pattern_ids"], d["kernel_mask"], d["pattern_masks"], x,
+                         d["bias"], relu=True)
+    np.testing.assert_allclose(got, want, atol=1e-12)
+    L.close()
+
+
+def test_worked_example_through_the_library():
+    g = read_golden_kv("fkw_worked_example.txt")
+    ids = np.zeros((4, 4), np.uint8)
+    mask = np.zeros((4, 4), np.uint8)
+    mask[0, [1, 3]] = 1; ids[0, 3] = 0; ids[0, 1] = 1
+    mask[1, [0, 2]] = 1; ids[1, 0] = 1; ids[1, 2] = 0
+    mask[2, [0, 1, 2]] = 1; ids[2, 0] = 0; ids[2, 1] = 1; ids[2, 2] = 0
+    mask[3, [2, 3]] = 1; ids[3, 2] = 0; ids[3, 3] = 0
+    lib = wl.pattern_universe()[[3, 40]]
+    w = np.random.default_rng(0).standard_normal((4, 4, 3, 3)).astype(np.float32)
+    L = B.Layer(w, ids, mask, lib, host_only=True)
+    f = L.export_fkw()
+    assert [str(v) for v in np.diff(f["offset"])] == g["filter_lengths_after_reorder"]
+    assert [str(v) for v in f["offset"][:4]] == g["offset"]
+    assert [str(v) for v in f["index"][:2]] == g["filter0_index"]
+    assert [str(v) for v in f["stride"][0]] == g["filter0_stride"]
+    a, b = (int(v) for v in g["swapped_filters"])
+    assert f["reorder"][a] == b and f["reorder"][b] == a
+    assert [str(4 * v) for v in np.diff(f["offset"])] == g["weights_per_filter"]
+    L.close()
+
+
+def test_degenerate_layers_roundtrip(oracle):
+    rng = np.random.default_rng(5)
+    lib = wl.pattern_library(3)
+    w = rng.standard_normal((5, 7, 3, 3)).astype(np.float32)
+    ids = rng.integers(0, 8, (5, 7), dtype=np.uint8)
+    for mask in (np.zeros((5, 7), np.uint8), np.ones((5, 7), np.uint8),
+                 np.eye(5, 7, dtype=np.uint8)):
+        L = B.Layer(w, ids, mask, lib, host_only=True)
+        dw, dids, dm = L.decode()
+        np.testing.assert_array_equal(dm, mask)
+        np.testing.assert_array_equal(dw, oracle.masked_weights(w, ids, mask, lib))
+        assert L.stats()["kept_kernels"] == mask.sum()
+        L.close()
+    # kernel_mask == NULL means every kernel kept
+    L = B.Layer(w, ids, None, lib, host_only=True)
+    assert L.decode()[2].all()
+    L.close()
+    # the id of a removed kernel is not read
+    ids2 = ids.copy(); ids2[1, 1] = 250
+    m = np.ones((5, 7), np.uint8); m[1, 1] = 0
+    B.Layer(w, ids2, m, lib, host_only=True).close()
+
+
+def test_error_reporting():
+    rng = np.random.default_rng(6)
+    lib = wl.pattern_library(3)
+    w = rng.standard_normal((4, 4, 3, 3)).astype(np.float32)
+    ids = rng.integers(0, 8, (4, 4), dtype=np.uint8)
+
+    def status(**kw):
+        args = dict(dense_weights=w, pattern_ids=ids, kernel_mask=None, pattern_masks=lib,
+                    flags=B.PATDNN_HOST_ONLY)
+        args.update(kw)
+        with pytest.raises(B.PatdnnError) as e:
+            B.patdnn_encode(**args)
+        return e.value.status
+
+    assert status(stride=3) == B.PATDNN_EINVAL
+    assert status(pad=2) == B.PATDNN_EINVAL
+    assert status(groups=2) == B.PATDNN_EINVAL
+    bad = lib.copy(); bad[2] = 0b111110000          # five positions
+    assert status(pattern_masks=bad) == B.PATDNN_EPATTERN
+    ids2 = ids.copy(); ids2[0, 0] = 8
+    assert status(pattern_ids=ids2) == B.PATDNN_EPATTERN
+    assert status(flags=B.PATDNN_HOST_ONLY | B.PATDNN_STRICT) == B.PATDNN_EPATTERN
+    # STRICT accepts a tensor that already obeys the constraints
+    from oracle import ref
+    h = B.patdnn_encode(ref.masked_weights(w, ids, None, lib), ids, None, lib,
+                        flags=B.PATDNN_HOST_ONLY | B.PATDNN_STRICT)
+    # a host-only handle cannot run
+    L = B.lib()
+    assert L.patdnn_conv2d(h, 1, 1, 8, 8, None, 1, 0, None) == B.PATDNN_EHIP
+    assert b"HOST_ONLY" in L.patdnn_last_error()
+    assert B.patdnn_output_shape(h, 2, 9, 10) == (2, 4, 9, 10)
+    with pytest.raises(B.PatdnnError):
+        B.patdnn_output_shape(h, 1, 0, 5)
+    B.patdnn_destroy(h)
+    B.patdnn_destroy(None)
+    assert L.patdnn_status_string(B.PATDNN_EPATTERN) == b"pattern constraint violated"
+
+
+def test_filter_groups_balance_after_reorder():
+    """Grouping filters by length (section 5.2) leaves the filter groups of the tiled
+    layout with nearly equal work: the spread inside the layer is a few percent."""
+    d = wl.gen_layer(2, 8, with_input=False)           # 512 -> 512
+    L = _host_layer(d)
+    st = L.stats()
+    assert st["group_size"] == 16 and st["filter_groups"] == 32
+    assert st["distinct_filter_lengths"] > 10                     # lengths do vary ...
+    mean = st["kept_kernels"] / st["filter_groups"]
+    assert st["max_group_kernels"] < 1.25 * mean                  # ... groups follow the sort
+    assert st["min_group_kernels"] > 0.75 * mean
+    L.close()
