@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Throughput benchmark of the pattern-sparse 3x3 convolution path on one MI355X.
+
+Workload: the VGG-16-shaped 13-layer 3x3 stack at 3x224x224, fp32, batch 64 - the
+throughput configuration (8-pattern library, connectivity keep ratio 1/3.6, first
+layer dense, He-normal weights, every layer on a seeded input of its own shape).
+A "step" is one pass over all 13 layers.  Inputs, weights and outputs are resident
+in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is effective GFLOP/s over non-zero FLOPs
+(2 x 4 x kept kernels x output pixels; 2 x 9 for the dense first layer).
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_VECTOR_TFLOPS = 157.3      # published; counts packed FP32 FMAs (2 per lane per clock)
+PEAK_FP32_NONPACKED_TFLOPS = 78.6    # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz
+
+
+def _log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload configuration (5 = N=64 VGG stack)")
+    ap.add_argument("--batch", type=int, default=None, help="override the batch size")
+    ap.add_argument("--no-tune", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense-compare", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2001_00138_amd import binding as B
+    from paper_2001_00138_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    B.lib()
+    torch.cuda.set_device(0)
+    stream = torch.cuda.current_stream()
+
+    # ------------------------------------------------------------------ set-up
+    specs = wl.config_layers(args.config)
+    layers = []
+    t_setup = time.time()
+    for li, spec in enumerate(specs):
+        d = wl.gen_layer(args.config, li, n=args.batch, with_input=False)
+        spec = d["spec"]
+        x = torch.empty((spec.n, spec.c_in, spec.h, spec.w), dtype=torch.float32, device="cuda")
+        for i in range(spec.n):
+            x[i].copy_(torch.from_numpy(wl.gen_input_image(spec, args.config, li, i)))
+        L = B.Layer.from_workload(d)
+        bias = torch.from_numpy(d["bias"]).cuda()
+        out = torch.empty(L.output_shape(spec.n, spec.h, spec.w), dtype=torch.float32, device="cuda")
+        kept = int(L.stats()["kept_kernels"])
+        if not args.no_tune:
+            L.tune(x, bias, out)
+        cfg = L.get_config()
+        layers.append(dict(spec=spec, d=d, L=L, x=x, bias=bias, out=out, kept=kept, cfg=cfg,
+                           nz=wl.nz_flops(spec, kept), dense_eq=wl.dense_flops(spec),
+                           bytes=wl.algorithmic_bytes(spec, kept)))
+        _log(f"[setup] {spec.name}: {spec.c_in}->{spec.c_out} @{spec.h} N={spec.n} kept={kept} "
+             f"cfg={cfg} ({B.patdnn_variant_name(max(cfg['variant'], 0))})")
+    torch.cuda.synchronize()
+    _log(f"[setup] done in {time.time() - t_setup:.1f} s")
+
+    def step(events=None):
+        for k, ly in enumerate(layers):
+            if events is not None:
+                events[k][0].record(stream)
+            ly["L"].conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+            if events is not None:
+                events[k][1].record(stream)
+
+    # ------------------------------------------------------------------ timed region
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in layers] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(ev[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    per_layer_ms = [float(np.mean([ev[s][k][0].elapsed_time(ev[s][k][1]) for s in range(args.steps)]))
+                    for k in range(len(layers))]
+    total_nz = sum(ly["nz"] for ly in layers)
+    total_dense = sum(ly["dense_eq"] for ly in layers)
+    value = total_nz / (ms_per_step * 1e-3) / 1e9
+
+    # ------------------------------------------------------------------ roofline of the dominant kernel
+    by_kernel = {}
+    for k, ly in enumerate(layers):
+        name = B.patdnn_variant_name(max(ly["cfg"]["variant"], 0))
+        if ly["spec"].dense or ly["spec"].depthwise:
+            continue
+        agg = by_kernel.setdefault(name, dict(ms=0.0, flops=0, bytes=0, launches=0))
+        agg["ms"] += per_layer_ms[k]
+        agg["flops"] += ly["nz"]
+        agg["bytes"] += ly["bytes"]
+        agg["launches"] += 1
+    roofline = None
+    if by_kernel:
+        kname, agg = max(by_kernel.items(), key=lambda kv: kv[1]["ms"])
+        achieved = agg["flops"] / (agg["ms"] * 1e-3) / 1e12
+        roofline = {
+            "bound": "alu", "kernel": kname, "achieved": round(achieved, 3),
+            "peak": PEAK_FP32_VECTOR_TFLOPS, "unit": "TFLOP/s",
+            "frac": round(achieved / PEAK_FP32_VECTOR_TFLOPS, 4),
+            "peak_nonpacked": PEAK_FP32_NONPACKED_TFLOPS,
+            "frac_nonpacked": round(achieved / PEAK_FP32_NONPACKED_TFLOPS, 4),
+            "launches_per_step": agg["launches"],
+            "avg_launch_ms": round(agg["ms"] / agg["launches"], 4),
+            "algorithmic_gflop_per_launch": round(agg["flops"] / agg["launches"] / 1e9, 3),
+            "algorithmic_gb_per_launch": round(agg["bytes"] / agg["launches"] / 1e9, 4),
+            "hbm_gbps_at_algorithmic_bytes": round(agg["bytes"] / (agg["ms"] * 1e-3) / 1e9, 1),
+            "traffic": None,
+        }
+
+    layer_rows = []
+    for k, ly in enumerate(layers):
+        spec = ly["spec"]
+        t = per_layer_ms[k] * 1e-3
+        layer_rows.append({
+            "layer": spec.name, "shape": f"{spec.c_in}->{spec.c_out}@{spec.h}", "kept": ly["kept"],
+            "variant": B.patdnn_variant_name(max(ly["cfg"]["variant"], 0)),
+            "ck": ly["cfg"]["ck"], "waves": ly["cfg"]["waves"],
+            "ms": round(per_layer_ms[k], 4),
+            "nz_gflops": round(ly["nz"] / t / 1e9, 1),
+            "dense_eq_gflops": round(ly["dense_eq"] / t / 1e9, 1),
+            "alg_gbps": round(ly["bytes"] / t / 1e9, 1),
+            "frac_alu_peak": round(ly["nz"] / t / 1e12 / PEAK_FP32_VECTOR_TFLOPS, 4),
+            "frac_hbm_peak": round(ly["bytes"] / t / 8e12, 4),
+        })
+
+    # ------------------------------------------------------------------ dense comparison (same shapes)
+    dense_cmp = None
+    if not args.no_dense_compare:
+        rows = []
+        for k, ly in enumerate(layers):
+            spec = ly["spec"]
+            if spec.depthwise:
+                continue
+            if spec.dense:
+                rows.append({"layer": spec.name, "dense_ms": round(per_layer_ms[k], 4)})
+                continue
+            Ld = B.Layer(ly["d"]["weights"], None, None, None, stride=spec.stride, pad=spec.pad, dense=True)
+            Ld.conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(2):
+                Ld.conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 2
+            rows.append({"layer": spec.name, "dense_ms": round(ms, 4),
+                         "dense_gflops": round(ly["dense_eq"] / (ms * 1e-3) / 1e9, 1),
+                         "speedup_pattern_vs_dense": round(ms / per_layer_ms[k], 2)})
+            Ld.close()
+        dense_cmp = rows
+
+    # ------------------------------------------------------------------ CPU oracle beside it
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ref
+        done_flops, spent, sample = 0, 0.0, []
+        for k, ly in enumerate(layers):
+            if spent >= args.cpu_seconds:
+                break
+            spec, d = ly["spec"], ly["d"]
+            x1 = ly["x"][:1].cpu().numpy()
+            c0 = time.perf_counter()
+            ref.conv2d(d["weights"], d["pattern_ids"], d["kernel_mask"], d["pattern_masks"], x1,
+                       d["bias"], stride=spec.stride, pad=spec.pad, relu=True, dense=spec.dense,
+                       skip_removed=True)
+            spent += time.perf_counter() - c0
+            done_flops += wl.nz_flops(spec, ly["kept"], n=1)
+            sample.append(spec.name)
+        cpu = {"value": round(done_flops / spent / 1e9, 3), "unit": "GFLOP/s", "cores": ref.num_threads(),
+               "kind": "oracle",
+               "sample": f"fp64 oracle, one image of layers {sample[0]}..{sample[-1]} "
+                         f"({len(sample)} layers, {spent:.1f} s)"}
+
+    spec0 = layers[0]["spec"]
+    result = {
+        "metric": "effective GFLOP/s (non-zero FLOPs) over the pattern-sparse VGG-16 3x3 conv stack",
+        "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.CONFIG_NAMES[args.config], "batch": spec0.n, "layers": len(layers),
+                   "patterns": 8, "connectivity_keep": "1/3.6", "input": "3x224x224" if args.config in (2, 5) else "per layer"},
+        "dense_equivalent_gflops": round(total_dense / (ms_per_step * 1e-3) / 1e9, 1),
+        "nz_gflop_per_step": round(total_nz / 1e9, 2),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "layers": layer_rows,
+        "dense_compare": dense_cmp,
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
