@@ -24,15 +24,15 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
 
 
 def sparse_geometries():
-    """(G, PR, PC, S) of every non-dense X(...) line of variants.def."""
+    """(G, PR, PC, S, TGX) of every non-dense X(...) line of variants.def."""
     geos = set()
     with open(os.path.join(CSRC, "variants.def")) as f:
         for line in f:
             if line.lstrip().startswith("//"):
                 continue
-            m = re.search(r"X\(\s*\w+\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*\d+\s*,\s*(true|false)", line)
-            if m and m.group(5) == "false":
-                geos.add(tuple(int(m.group(i)) for i in range(1, 5)))
+            m = re.search(r"X\(\s*\w+\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(true|false)", line)
+            if m and m.group(6) == "false":
+                geos.add(tuple(int(m.group(i)) for i in range(1, 6)))
     return sorted(geos)
 
 

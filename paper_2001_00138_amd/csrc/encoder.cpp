@@ -179,19 +179,32 @@ void decode_fkw(const LayerHost& L, const Fkw& f, float* w, uint8_t* ids, uint8_
     }
 }
 
-void build_tiled(const LayerHost& L, int G, Tiled& T)
+void build_tiled(const LayerHost& L, const TiledParams& prm, Tiled& T)
 {
     const Fkw& f = L.fkw;
+    const int G = prm.G;
     const int c_out = L.desc.c_out, c_in = L.desc.c_in, P = f.num_patterns;
     T = Tiled();
     T.G = G;
     T.dense = L.dense;
     T.num_groups = (c_out + G - 1) / G;
     T.slot_channel.assign((size_t)T.num_groups * G, -1);
+    T.group_kernels.assign(T.num_groups, 0);
+    if (L.dense) {
+        T.w9.assign((size_t)T.num_groups * c_in * G * 9, 0.0f);
+    } else {
+        T.ck = prm.ck;
+        T.num_chunks = (c_in + prm.ck - 1) / prm.ck;
+        T.chunk_ptr.assign((size_t)T.num_groups * T.num_chunks, 0);
+    }
 
     struct Entry { uint32_t chan, upat, slot; int32_t k; };
-    if (L.dense) T.w9.assign((size_t)T.num_groups * c_in * G * 9, 0.0f);
-    else T.chan_ptr.assign((size_t)T.num_groups * (c_in + 1), 0);
+    auto push = [&](uint32_t target, float p0, float p1, float p2, float p3) {
+        T.target.push_back(target);
+        const float p[4] = {p0, p1, p2, p3};
+        T.payload.insert(T.payload.end(), p, p + 4);
+    };
+    auto bits_as_float = [](uint32_t v) { float fl; std::memcpy(&fl, &v, 4); return fl; };
 
     std::vector<Entry> ent;
     for (int g = 0; g < T.num_groups; ++g) {
@@ -201,6 +214,7 @@ void build_tiled(const LayerHost& L, int G, Tiled& T)
             if (r >= c_out) break;
             const int s = c_out - 1 - r;              // FKW position (lengths ascend there)
             T.slot_channel[(size_t)g * G + slot] = f.reorder[s];
+            T.group_kernels[g] += f.offset[s + 1] - f.offset[s];
             const int32_t* st = &f.stride[(size_t)s * (P + 1)];
             for (int p = 0; p < P; ++p)
                 for (int32_t k = f.offset[s] + st[p]; k < f.offset[s] + st[p + 1]; ++k) {
@@ -218,18 +232,27 @@ void build_tiled(const LayerHost& L, int G, Tiled& T)
             if (a.upat != b.upat) return a.upat < b.upat;
             return a.slot < b.slot;
         });
-        uint32_t* cp = &T.chan_ptr[(size_t)g * (c_in + 1)];
-        const uint32_t base = (uint32_t)T.code.size();
         size_t e = 0;
-        for (int c = 0; c <= c_in; ++c) {
-            while (e < ent.size() && (int)ent[e].chan < c) ++e;
-            cp[c] = base + (uint32_t)e;
+        for (int chunk = 0; chunk < T.num_chunks; ++chunk) {
+            T.chunk_ptr[(size_t)g * T.num_chunks + chunk] = (uint32_t)T.target.size();
+            const uint32_t c_end = (uint32_t)std::min(c_in, (chunk + 1) * prm.ck);
+            uint32_t cur = UINT32_MAX;
+            for (; e < ent.size() && ent[e].chan < c_end; ++e) {
+                const Entry& x = ent[e];
+                if (x.chan != cur) {
+                    cur = x.chan;
+                    push(prm.loadwin_off, bits_as_float((cur - (uint32_t)chunk * prm.ck) * prm.channel_bytes),
+                         0.0f, 0.0f, 0.0f);
+                }
+                const float* w = &f.weight[(size_t)x.k * 4];
+                push((x.slot * (uint32_t)kUniverse + x.upat) * prm.block_bytes, w[0], w[1], w[2], w[3]);
+            }
+            push(prm.end_off, 0.0f, 0.0f, 0.0f, 0.0f);
         }
-        for (const Entry& x : ent) {
-            T.code.push_back((x.chan << 16) | (x.slot * (uint32_t)kUniverse + x.upat));
-            const float* src = &f.weight[(size_t)x.k * 4];
-            T.w4.insert(T.w4.end(), src, src + 4);
-        }
+    }
+    if (!L.dense) {
+        // the interpreter requests `batch` records at a time, two requests ahead of use
+        for (uint32_t i = 0; i < 3 * prm.batch; ++i) push(prm.end_off, 0.0f, 0.0f, 0.0f, 0.0f);
     }
 }
 

@@ -14,11 +14,17 @@
 //     it: the window is reused across the taps and output rows of a kernel
 //     (kernel-level load-redundancy elimination, section 5.4) and across the
 //     filters of the group (filter-level elimination).
-//   * Each kept kernel is one wave-uniform computed jump on (filter slot, pattern) into
-//     a straight-line body of 4*PR*PC FMAs with the weights as scalar operands - one
-//     generated body per pattern, no indirect addressing, no per-lane branches
-//     (section 5.2 / 5.4).  The pattern index ranges over the 56 centre-keeping
-//     patterns of section 4.1.
+//   * The kept kernels of a group reach the wavefront as a record stream written by
+//     the encoder ("load window of channel c", "kernel: slot, pattern, 4 weights",
+//     "end of chunk").  A generated interpreter (gen_dispatch.py) reads it over the
+//     scalar data path and jumps, per record, into a straight-line block of 4*PR*PC
+//     FMAs with the weights as scalar operands - one generated body per pattern, no
+//     indirect addressing, no per-lane branches (section 5.2 / 5.4).  The pattern
+//     index ranges over the 56 centre-keeping patterns of section 4.1.
+//   * Dense (unpruned) layers use the same staging and register tiling with a plain
+//     9-tap loop and no stream.
+#include <type_traits>
+
 #include "kernels.hpp"
 #include "layout.hpp"
 
@@ -29,12 +35,12 @@ struct TiledArgs {
     const float* bias;
     float* out;
     const int32_t* slot_channel;
-    const uint32_t* chan_ptr;
-    const uint32_t* code;
-    const float* w4;
+    const uint32_t* chunk_ptr;
+    const uint32_t* target;
+    const float* payload;
     const float* w9;
     int32_t n, c_in, c_out, h, w, ho, wo, pad, relu;
-    int32_t num_groups, bx, by, num_bands, ck, waves, fgsets;
+    int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets;
 };
 
 template <int G_, int PR_, int PC_, int S_, int TGX_, bool DENSE_, int MAXSLOTS_>
@@ -53,11 +59,16 @@ struct Geo {
     static constexpr int NACC = PR * PC;
 };
 
-// Dispatch<G,PR,PC,S>::run(acc, win, w0..w3, idx): the pattern-specialised FMA bodies,
-// generated by gen_dispatch.py (one straight-line block per filter slot and pattern,
-// reached by a computed jump on idx = slot*56 + pattern).
-template <int G, int PR, int PC, int S>
-struct Dispatch;
+// StreamLoop<G,PR,PC,S,TGX>::run(acc, lane_lds, targets, payload, start): the record
+// interpreter with its table of pattern-specialised FMA blocks (gen_dispatch.py).
+template <int G, int PR, int PC, int S, int TGX>
+struct StreamLoop;
+
+// dense variants have no stream
+template <int G, int PR, int PC, int S, int TGX>
+struct NoStream {
+    static constexpr unsigned kBlockBytes = 0, kEndOff = 0, kLoadWinOff = 0, kBatch = 0;
+};
 
 #include "gen/dispatch_all.inc"
 
@@ -69,8 +80,6 @@ __device__ __forceinline__ T load_uniform(const T* p, size_t i)
     typedef const T __attribute__((address_space(4))) * cptr;
     return ((cptr)(uintptr_t)p)[i];
 }
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <class GEO>
 __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
@@ -128,7 +137,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
         oy0 = byi * PR;
         ox0 = (bxi * TGX + gx) * PC;
     }
-    const float* lane_lds = lds + lb * GEO::BANDP + gx * PC * S;
+    const int lane_off = lb * GEO::BANDP + gx * PC * S;      // floats, inside one staged channel
 
     float acc[G][GEO::NACC];
 #pragma unroll
@@ -137,9 +146,8 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
         for (int i = 0; i < GEO::NACC; ++i) acc[s][i] = 0.0f;
 
     const bool group_ok = group < a.num_groups;
-    const uint32_t* cp = a.chan_ptr + (size_t)(group_ok ? group : 0) * (a.c_in + 1);
 
-    for (int c0 = 0; c0 < a.c_in; c0 += a.ck) {
+    for (int c0 = 0, chunk = 0; c0 < a.c_in; c0 += a.ck, ++chunk) {
         const int cn = min(a.ck, a.c_in - c0);
         // ---- stage cn channels of the NB bands into LDS
         for (int c = 0; c < cn; ++c) {
@@ -157,7 +165,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
             if constexpr (GEO::DENSE) {
                 for (int c = 0; c < cn; ++c) {
                     float win[WR * WC];
-                    const float* base = lane_lds + c * GEO::TILEP;
+                    const float* base = lds + lane_off + c * GEO::TILEP;
 #pragma unroll
                     for (int q = 0; q < WR; ++q)
 #pragma unroll
@@ -178,34 +186,12 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                         }
                 }
             } else {
-                uint32_t e = load_uniform(cp, c0);
-                const uint32_t e_end = load_uniform(cp, c0 + cn);
-                int cur = -1;
-                float win[WR * WC];
-                // entries are fetched one ahead over the scalar data path; the arrays
-                // carry a dummy entry past the end so that the fetch is unconditional
-                uint32_t code_n = load_uniform(a.code, e);
-                f32x4 w_n = load_uniform(reinterpret_cast<const f32x4*>(a.w4), e);
-                while (e < e_end) {
-                    const uint32_t cd = code_n;
-                    const f32x4 wv = w_n;
-                    ++e;
-                    const int c = (int)(cd >> 16);
-                    if (c != cur) {
-                        cur = c;
-                        const float* base = lane_lds + (c - c0) * GEO::TILEP;
-#pragma unroll
-                        for (int q = 0; q < WR; ++q)
-#pragma unroll
-                            for (int r = 0; r < WC; ++r) win[q * WC + r] = base[q * PITCH + r];
-                        // wait for the window here, before the next entry is requested, so
-                        // that the request below stays in flight across the FMA block
-                        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
-                    }
-                    code_n = load_uniform(a.code, e);
-                    w_n = load_uniform(reinterpret_cast<const f32x4*>(a.w4), e);
-                    Dispatch<G, PR, PC, S>::run(acc, win, wv.x, wv.y, wv.z, wv.w, cd & 0xFFFFu);
-                }
+                // the group's records of this chunk: window loads, kernels, end marker
+                const unsigned start = load_uniform(a.chunk_ptr, (size_t)group * a.num_chunks + chunk);
+                const unsigned lds_base =
+                    (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
+                StreamLoop<G, PR, PC, S, TGX>::run(acc, lds_base + 4u * (unsigned)lane_off, a.target,
+                                                   a.payload, start);
             }
         }
         __syncthreads();
@@ -235,12 +221,12 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
 
 template <class GEO>
 static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const float* in,
-                               const float* bias, float* out, int32_t ck, int32_t waves,
-                               hipStream_t stream)
+                               const float* bias, float* out, int32_t waves, hipStream_t stream)
 {
     TiledArgs a{};
     a.in = in; a.bias = bias; a.out = out;
-    a.slot_channel = t.slot_channel; a.chan_ptr = t.chan_ptr; a.code = t.code; a.w4 = t.w4; a.w9 = t.w9;
+    a.slot_channel = t.slot_channel; a.chunk_ptr = t.chunk_ptr; a.target = t.target;
+    a.payload = t.payload; a.w9 = t.w9;
     a.n = s.n; a.c_in = s.c_in; a.c_out = s.c_out; a.h = s.h; a.w = s.w; a.ho = s.ho; a.wo = s.wo;
     a.pad = s.pad; a.relu = s.relu;
     a.num_groups = t.num_groups;
@@ -249,29 +235,31 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
     const long long bands = (long long)s.n * a.bx * a.by;
     const long long tiles = (bands + GEO::NB - 1) / GEO::NB;
     a.num_bands = (int32_t)bands;
-    a.ck = ck; a.waves = waves;
+    a.ck = t.ck; a.num_chunks = t.num_chunks; a.waves = waves;
     a.fgsets = (t.num_groups + waves - 1) / waves;
     const long long blocks = tiles * a.fgsets;
     if (bands > INT32_MAX || blocks > INT32_MAX) return hipErrorInvalidValue;
-    const size_t lds_bytes = (size_t)ck * GEO::TILEP * sizeof(float);
+    const size_t lds_bytes = (size_t)t.ck * GEO::TILEP * sizeof(float);
     hipLaunchKernelGGL(tiled_conv_kernel<GEO>, dim3((unsigned)blocks), dim3(64 * waves), lds_bytes,
                        stream, a);
     return hipGetLastError();
 }
 
 // X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS) - one line per compiled variant
-#define PATDNN_TILED_VARIANT_LIST
 #include "variants.def"
-#undef PATDNN_TILED_VARIANT_LIST
 
-#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS) using Geo_##name = Geo<G, PR, PC, S, TGX, DENSE, MAXSLOTS>;
+#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS)                                        \
+    using Geo_##name = Geo<G, PR, PC, S, TGX, DENSE, MAXSLOTS>;                            \
+    using Stream_##name = std::conditional<DENSE, NoStream<G, PR, PC, S, TGX>,             \
+                                           StreamLoop<G, PR, PC, S, TGX>>::type;
 PATDNN_VARIANTS
 #undef X
 
 static const TiledVariant kVariants[] = {
-#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS)                                      \
-    {#name, G, PR, PC, S, TGX, DENSE, Geo_##name::TILEP, Geo_##name::NB * Geo_##name::BAND, MAXSLOTS, \
-     &launch_tiled<Geo_##name>},
+#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS)                                        \
+    {#name, G, PR, PC, S, TGX, DENSE, Geo_##name::TILEP, Geo_##name::NB * Geo_##name::BAND, \
+     MAXSLOTS, Stream_##name::kBlockBytes, Stream_##name::kEndOff, Stream_##name::kLoadWinOff, \
+     Stream_##name::kBatch, &launch_tiled<Geo_##name>},
     PATDNN_VARIANTS
 #undef X
 };

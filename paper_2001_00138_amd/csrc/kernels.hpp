@@ -23,14 +23,16 @@ struct DevFkw {
     int32_t taps = 4;
 };
 
-// Channel-major filter-group layout on the device.
+// Filter-group layout on the device: record streams (sparse) or 9-tap weights (dense).
 struct DevTiled {
     int32_t G = 0;
     int32_t num_groups = 0;
+    int32_t ck = 0;            // input channels staged per LDS pass (fixes the chunking of the streams)
+    int32_t num_chunks = 0;
     const int32_t* slot_channel = nullptr;
-    const uint32_t* chan_ptr = nullptr;
-    const uint32_t* code = nullptr;
-    const float* w4 = nullptr;
+    const uint32_t* chunk_ptr = nullptr;   // [num_groups][num_chunks] first record of a chunk
+    const uint32_t* target = nullptr;      // [records] byte offset of the record's code block
+    const float* payload = nullptr;        // [records][4]
     const float* w9 = nullptr;
 };
 
@@ -51,8 +53,13 @@ struct TiledVariant {
     int32_t lds_floats_per_channel;   // LDS floats one staged channel takes
     int32_t stage_elems;              // elements staged per channel (without bank padding)
     int32_t max_slots;                // staging elements per thread the kernel can hold
+    // code-table geometry of the record interpreter (sparse variants)
+    uint32_t block_bytes;             // size of one (slot, pattern) block; block i at i*block_bytes
+    uint32_t end_off;                 // offset of the end-of-chunk block
+    uint32_t loadwin_off;             // offset of the window-load block
+    uint32_t batch;                   // records fetched per scalar request
     hipError_t (*launch)(const DevTiled&, const ConvShape&, const float*, const float*, float*,
-                         int32_t ck, int32_t waves, hipStream_t);
+                         int32_t waves, hipStream_t);
 };
 
 int num_tiled_variants();

@@ -49,25 +49,40 @@ struct Fkw {
 };
 
 // ---------------------------------------------------------------------------
-// Tiled layout for one group size G.  Filters are taken G at a time from the FKR
-// order, longest first; inside a group the kept kernels are listed channel-major so
-// that one staged input window serves every kernel of the group on that channel
-// (filter-level load-redundancy elimination, section 5.4).
+// Tiled layout for one kernel variant.  Filters are taken G at a time from the FKR
+// order, longest first.  Sparse layers: per filter group and per chunk of `ck` input
+// channels, a stream of records that the kernel's interpreter executes in order -
+//   "load window"  target = loadwin_off, payload[0] = byte offset of the channel inside
+//                  the staged chunk (bit pattern of an integer)
+//   "kernel"       target = (slot*56 + universe index) * block_bytes, payload = 4 weights
+//   "end"          target = end_off
+// Kernels are listed channel-major so that one window load serves every kernel of the
+// group on that channel (filter-level load-redundancy elimination, section 5.4), and
+// by pattern inside a channel (kernel reorder, section 5.2).
 // ---------------------------------------------------------------------------
+struct TiledParams {
+    int32_t G = 0;
+    int32_t ck = 0;                      // channels per chunk (sparse only)
+    uint32_t block_bytes = 0, end_off = 0, loadwin_off = 0, batch = 0;
+    uint32_t channel_bytes = 0;          // LDS bytes of one staged channel
+};
+
 struct Tiled {
     int32_t G = 0;
     int32_t num_groups = 0;
+    int32_t ck = 0, num_chunks = 0;
     bool dense = false;
     std::vector<int32_t> slot_channel;   // [num_groups*G] original output channel, -1 = empty slot
+    std::vector<int64_t> group_kernels;  // [num_groups] kept kernels per group
     // sparse layers
-    std::vector<uint32_t> chan_ptr;      // [num_groups][c_in+1] entry ranges per input channel
-    std::vector<uint32_t> code;          // [kept] (channel << 16) | (slot * 56 + universe index)
-    std::vector<float> w4;               // [kept][4]
+    std::vector<uint32_t> chunk_ptr;     // [num_groups][num_chunks]
+    std::vector<uint32_t> target;        // [records + padding]
+    std::vector<float> payload;          // [records + padding][4]
     // dense layers
     std::vector<float> w9;               // [num_groups][c_in][G][9]
     size_t bytes() const
     {
-        return 4 * (slot_channel.size() + chan_ptr.size() + code.size() + w4.size() + w9.size());
+        return 4 * (slot_channel.size() + chunk_ptr.size() + target.size() + payload.size() + w9.size());
     }
 };
 
@@ -85,8 +100,8 @@ struct LayerHost {
 patdnn_status_t build_fkw(const patdnn_layer_desc_t& d, const float* w, const uint8_t* ids,
                           const uint8_t* mask, LayerHost& out, std::string& err);
 
-// Channel-major group layout derived from the FKW arrays.
-void build_tiled(const LayerHost& L, int G, Tiled& out);
+// Filter-group layout of one variant, derived from the FKW arrays.
+void build_tiled(const LayerHost& L, const TiledParams& p, Tiled& out);
 
 // Inverse of build_fkw from the five arrays (any output may be null).
 void decode_fkw(const LayerHost& L, const Fkw& f, float* w, uint8_t* ids, uint8_t* mask);

@@ -9,6 +9,7 @@
 #include <memory>
 #include <new>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "kernels.hpp"
@@ -44,7 +45,8 @@ struct patdnn_layer {
     bool on_device = false;
     int device = -1;
     DevFkw dfkw;
-    std::map<int, std::unique_ptr<TiledOnDevice>> tiled;   // by group size G
+    // by (variant index, ck); dense variants use ck = 0
+    std::map<std::pair<int, int>, std::unique_ptr<TiledOnDevice>> tiled;
     std::vector<void*> allocations;
     patdnn_config_t cfg{-1, 0, 0, 0};                      // variant -1: choose per call
 
@@ -92,6 +94,12 @@ bool variant_fits_layer(const patdnn_layer* h, const TiledVariant& v)
 constexpr int kMaxLdsBytes = 64 * 1024;
 constexpr int kMaxWaves = 8;
 
+int default_ck(const TiledVariant& v, int c_in)
+{
+    const int max_ck = kMaxLdsBytes / (4 * v.lds_floats_per_channel);
+    return std::max(1, std::min(std::min(8, max_ck), c_in));
+}
+
 // Smallest / default launch parameters of a tiled variant for this layer; false if
 // the variant cannot run at all.
 bool resolve_tiled_params(const patdnn_layer* h, const TiledVariant& v, const ConvShape& s,
@@ -104,7 +112,7 @@ bool resolve_tiled_params(const patdnn_layer* h, const TiledVariant& v, const Co
     if (waves < min_waves || waves > kMaxWaves) return false;
     const int max_ck = kMaxLdsBytes / (4 * v.lds_floats_per_channel);
     if (max_ck < 1) return false;
-    if (ck <= 0) ck = std::min(std::min(8, max_ck), s.c_in);
+    if (ck <= 0) ck = default_ck(v, s.c_in);
     if (ck < 1 || ck > max_ck) return false;
     // staging offsets are 32-bit, relative to the first image of a tile
     const int nb = 64 / v.TGX;
@@ -113,26 +121,38 @@ bool resolve_tiled_params(const patdnn_layer* h, const TiledVariant& v, const Co
     return true;
 }
 
-patdnn_status_t ensure_tiled(patdnn_layer* h, int G, const DevTiled** out)
+patdnn_status_t ensure_tiled(patdnn_layer* h, int vi, int ck, const DevTiled** out)
 {
-    auto it = h->tiled.find(G);
+    const TiledVariant& v = tiled_variant(vi);
+    if (v.dense) ck = 0;
+    const std::pair<int, int> key(vi, ck);
+    auto it = h->tiled.find(key);
     if (it == h->tiled.end()) {
         std::unique_ptr<TiledOnDevice> t(new (std::nothrow) TiledOnDevice());
         if (!t) return fail(PATDNN_ENOMEM, "out of host memory");
-        build_tiled(h->L, G, t->host);
-        t->dev.G = G;
+        TiledParams prm;
+        prm.G = v.G;
+        prm.ck = ck;
+        prm.block_bytes = v.block_bytes;
+        prm.end_off = v.end_off;
+        prm.loadwin_off = v.loadwin_off;
+        prm.batch = v.batch;
+        prm.channel_bytes = 4u * (uint32_t)v.lds_floats_per_channel;
+        build_tiled(h->L, prm, t->host);
+        t->dev.G = v.G;
         t->dev.num_groups = t->host.num_groups;
+        t->dev.ck = ck;
+        t->dev.num_chunks = t->host.num_chunks;
         if (h->on_device) {
             hipError_t e;
             if ((e = upload(h, t->host.slot_channel, &t->dev.slot_channel)) != hipSuccess ||
-                (e = upload(h, t->host.chan_ptr, &t->dev.chan_ptr)) != hipSuccess ||
-                // one dummy entry past the end: the kernel fetches one entry ahead
-                (e = upload(h, t->host.code, &t->dev.code, 1)) != hipSuccess ||
-                (e = upload(h, t->host.w4, &t->dev.w4, 4)) != hipSuccess ||
+                (e = upload(h, t->host.chunk_ptr, &t->dev.chunk_ptr)) != hipSuccess ||
+                (e = upload(h, t->host.target, &t->dev.target)) != hipSuccess ||
+                (e = upload(h, t->host.payload, &t->dev.payload)) != hipSuccess ||
                 (e = upload(h, t->host.w9, &t->dev.w9)) != hipSuccess)
                 return hip_fail(e, "uploading the tiled layout");
         }
-        it = h->tiled.emplace(G, std::move(t)).first;
+        it = h->tiled.emplace(key, std::move(t)).first;
     }
     if (out) *out = &it->second->dev;
     return PATDNN_OK;
@@ -171,9 +191,14 @@ patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const Conv
     if (!resolve_tiled_params(h, v, s, ck, waves))
         return fail(PATDNN_EUNSUPPORTED, "launch parameters outside the variant's limits");
     const DevTiled* t = nullptr;
-    patdnn_status_t st = ensure_tiled(h, v.G, &t);
-    if (st != PATDNN_OK) return st;
-    hipError_t e = v.launch(*t, s, in, bias, out, ck, waves, stream);
+    // the layout of (variant, ck) is built by encode / set_config / tune, never here
+    auto it = h->tiled.find(std::make_pair(vi, v.dense ? 0 : ck));
+    if (it == h->tiled.end())
+        return fail(PATDNN_EUNSUPPORTED, "no layout for this ck: choose it with patdnn_set_config");
+    t = &it->second->dev;
+    DevTiled dt = *t;
+    if (v.dense) { dt.ck = ck; dt.num_chunks = (s.c_in + ck - 1) / ck; }
+    hipError_t e = v.launch(dt, s, in, bias, out, waves, stream);
     return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching a tiled kernel");
 }
 
@@ -229,7 +254,7 @@ patdnn_status_t patdnn_encode(const patdnn_layer_desc_t* desc, const float* dens
     try {
         for (int vi = 0; vi < num_tiled_variants(); ++vi)
             if (variant_fits_layer(h.get(), tiled_variant(vi))) {
-                st = ensure_tiled(h.get(), tiled_variant(vi).G, nullptr);
+                st = ensure_tiled(h.get(), vi, default_ck(tiled_variant(vi), desc->c_in), nullptr);
                 if (st != PATDNN_OK) return st;
             }
     } catch (const std::bad_alloc&) {
@@ -354,17 +379,9 @@ patdnn_status_t patdnn_layout_stats(patdnn_handle_t h, patdnn_stats_t* out)
         const Tiled& t = h->tiled.begin()->second->host;
         out->filter_groups = t.num_groups;
         out->group_size = t.G;
-        if (!t.dense && t.num_groups > 0) {
-            int64_t mx = 0, mn = INT64_MAX;
-            const int c_in = h->L.desc.c_in;
-            for (int g = 0; g < t.num_groups; ++g) {
-                const int64_t k = (int64_t)t.chan_ptr[(size_t)g * (c_in + 1) + c_in] -
-                                  (int64_t)t.chan_ptr[(size_t)g * (c_in + 1)];
-                mx = std::max(mx, k);
-                mn = std::min(mn, k);
-            }
-            out->max_group_kernels = mx;
-            out->min_group_kernels = mn;
+        if (!t.group_kernels.empty()) {
+            out->max_group_kernels = *std::max_element(t.group_kernels.begin(), t.group_kernels.end());
+            out->min_group_kernels = *std::min_element(t.group_kernels.begin(), t.group_kernels.end());
         }
     }
     return PATDNN_OK;
@@ -400,6 +417,17 @@ patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
     }
     h->cfg = *cfg;
     h->cfg.reserved = 0;
+    if (cfg->variant > 0) {
+        const TiledVariant& v = tiled_variant(cfg->variant - 1);
+        if (h->cfg.ck == 0) h->cfg.ck = default_ck(v, h->L.desc.c_in);
+        h->cfg.ck = std::min(h->cfg.ck, h->L.desc.c_in);
+        try {
+            patdnn_status_t st = ensure_tiled(h, cfg->variant - 1, h->cfg.ck, nullptr);
+            if (st != PATDNN_OK) return st;
+        } catch (const std::bad_alloc&) {
+            return fail(PATDNN_ENOMEM, "out of host memory");
+        }
+    }
     return PATDNN_OK;
 }
 
@@ -433,6 +461,7 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
                 int32_t ck2 = std::min(ck, s.c_in), w2 = waves;
                 if (w2 > 1 && w2 / 2 >= groups) continue;      // mostly idle wavefronts
                 if (!resolve_tiled_params(h, v, s, ck2, w2)) continue;
+                if (ensure_tiled(h, vi, ck2, nullptr) != PATDNN_OK) continue;
                 patdnn_config_t c{vi + 1, ck2, w2, 0};
                 bool dup = false;
                 for (const auto& o : cands) dup |= (o.variant == c.variant && o.ck == c.ck && o.waves == c.waves);
