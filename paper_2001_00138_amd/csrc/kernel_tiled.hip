@@ -8,7 +8,10 @@
 //   * A workgroup is `waves` wavefronts that share the same NB bands and take
 //     consecutive filter groups.  Input channels are staged through LDS, `ck`
 //     channels at a time, band by band with a one-pixel halo, zero-filled outside
-//     the image (the paper's input tiling, section 5.4).
+//     the image (the paper's input tiling, section 5.4).  Staging uses buffer loads
+//     that write LDS directly (no registers; out-of-image lanes carry an out-of-range
+//     offset and read as zero) into two alternating LDS buffers, so the loads of chunk
+//     k+1 are in flight while chunk k is computed.
 //   * Per staged channel a lane loads its (PR-1)*S+3 x (PC-1)*S+3 input window into
 //     registers ONCE and applies every kept kernel of the group on that channel to
 //     it: the window is reused across the taps and output rows of a kernel
@@ -55,7 +58,9 @@ struct Geo {
     // bands start 16 banks apart (mod 64) so that the NB bands of a wavefront do not
     // collide on LDS banks when every lane reads the same window element
     static constexpr int BANDP = NB == 1 ? BAND : BAND + ((16 - BAND % 64) + 64) % 64;
-    static constexpr int TILEP = NB * BANDP;            // LDS floats per staged channel
+    // LDS floats per staged channel; a multiple of 64 because every staging instruction
+    // of a wavefront fills 64 consecutive dwords
+    static constexpr int TILEP = (NB * BANDP + 63) / 64 * 64;
     static constexpr int NACC = PR * PC;
 };
 
@@ -81,6 +86,8 @@ __device__ __forceinline__ T load_uniform(const T* p, size_t i)
     return ((cptr)(uintptr_t)p)[i];
 }
 
+typedef __attribute__((address_space(3))) float lds_f32;
+
 template <class GEO>
 __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
 {
@@ -102,17 +109,17 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     const int img0 = band0 / (a.bx * a.by);
     const float* in_blk = a.in + (size_t)img0 * a.c_in * plane;
 
-    // ---- staging slots of this thread: where each element comes from / goes to
-    int goff[GEO::MAXSLOTS], loff[GEO::MAXSLOTS];
+    // ---- staging slots of this thread: byte offset (inside the tile's first image
+    // onwards) of the input element that lands in LDS dword tid + k*nthreads of a staged
+    // channel; ~0u (out of range for the buffer descriptor, reads as zero) for padding
+    unsigned voff[GEO::MAXSLOTS];
 #pragma unroll
     for (int k = 0; k < GEO::MAXSLOTS; ++k) {
         const int e = tid + k * nthreads;
-        goff[k] = -1;
-        loff[k] = -1;
-        if (e < NB * GEO::BAND) {
-            const int b = e / GEO::BAND, rem = e - b * GEO::BAND;
+        voff[k] = ~0u;
+        const int b = e / GEO::BANDP, rem = e - b * GEO::BANDP;
+        if (b < NB && rem < GEO::BAND) {
             const int q = rem / PITCH, x = rem - q * PITCH;
-            loff[k] = b * GEO::BANDP + rem;
             const int band = band0 + b;
             if (band < a.num_bands) {
                 const int bxi = band % a.bx, t = band / a.bx;
@@ -120,10 +127,32 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                 const int iy = byi * PR * S - a.pad + q;
                 const int ix = bxi * TGX * PC * S - a.pad + x;
                 if (iy >= 0 && iy < a.h && ix >= 0 && ix < a.w)
-                    goff[k] = (img - img0) * a.c_in * plane + iy * a.w + ix;
+                    voff[k] = 4u * (unsigned)((img - img0) * a.c_in * plane + iy * a.w + ix);
             }
         }
     }
+    // bytes from the tile's first image to the end of the input tensor
+    const size_t blk_bytes = (size_t)(a.n - img0) * a.c_in * plane * 4;
+    lds_f32* const lds3 = (lds_f32*)lds;
+    const int buf_floats = a.ck * GEO::TILEP;
+
+    auto stage = [&](int c0, lds_f32* buf) {
+        const int cn = min(a.ck, a.c_in - c0);
+        for (int c = 0; c < cn; ++c) {
+            const size_t off = (size_t)(c0 + c) * plane * 4;
+            const size_t left = blk_bytes - off;
+            const unsigned nrec = left > 0xFFFFFFFFull ? 0xFFFFFFFFu : (unsigned)left;
+            __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                (void*)((const char*)in_blk + off), 0, (int)nrec, 0x00020000);
+#pragma unroll
+            for (int k = 0; k < GEO::MAXSLOTS; ++k) {
+                const int eb = wave * 64 + k * nthreads;          // wave-uniform
+                if (eb < GEO::TILEP)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, buf + c * GEO::TILEP + eb, 4,
+                                                             (int)voff[k], 0, 0, 0);
+            }
+        }
+    };
 
     // ---- this lane's patch
     const int lb = lane / TGX, gx = lane - lb * TGX;
@@ -147,25 +176,21 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
 
     const bool group_ok = group < a.num_groups;
 
+    stage(0, lds3);
     for (int c0 = 0, chunk = 0; c0 < a.c_in; c0 += a.ck, ++chunk) {
         const int cn = min(a.ck, a.c_in - c0);
-        // ---- stage cn channels of the NB bands into LDS
-        for (int c = 0; c < cn; ++c) {
-            const float* src = in_blk + (size_t)(c0 + c) * plane;
-            float v[GEO::MAXSLOTS];
-#pragma unroll
-            for (int k = 0; k < GEO::MAXSLOTS; ++k) v[k] = goff[k] >= 0 ? src[goff[k]] : 0.0f;
-#pragma unroll
-            for (int k = 0; k < GEO::MAXSLOTS; ++k)
-                if (loff[k] >= 0) lds[c * GEO::TILEP + loff[k]] = v[k];
-        }
+        const int cur = (chunk & 1) * buf_floats;
+        // chunk `chunk` has landed in this wavefront's view, and (barrier) in everyone's;
+        // everyone has also finished reading the other buffer
+        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
         __syncthreads();
+        if (c0 + a.ck < a.c_in) stage(c0 + a.ck, lds3 + (buf_floats - cur));
 
         if (group_ok) {
             if constexpr (GEO::DENSE) {
                 for (int c = 0; c < cn; ++c) {
                     float win[WR * WC];
-                    const float* base = lds + lane_off + c * GEO::TILEP;
+                    const float* base = lds + cur + lane_off + c * GEO::TILEP;
 #pragma unroll
                     for (int q = 0; q < WR; ++q)
 #pragma unroll
@@ -190,11 +215,10 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                 const unsigned start = load_uniform(a.chunk_ptr, (size_t)group * a.num_chunks + chunk);
                 const unsigned lds_base =
                     (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
-                StreamLoop<G, PR, PC, S, TGX>::run(acc, lds_base + 4u * (unsigned)lane_off, a.target,
+                StreamLoop<G, PR, PC, S, TGX>::run(acc, lds_base + 4u * (unsigned)(cur + lane_off), a.target,
                                                    a.payload, start);
             }
         }
-        __syncthreads();
     }
 
     // ---- epilogue: bias, ReLU, scatter to the original output channel
@@ -239,7 +263,14 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
     a.fgsets = (t.num_groups + waves - 1) / waves;
     const long long blocks = tiles * a.fgsets;
     if (bands > INT32_MAX || blocks > INT32_MAX) return hipErrorInvalidValue;
-    const size_t lds_bytes = (size_t)t.ck * GEO::TILEP * sizeof(float);
+    const size_t lds_bytes = 2 * (size_t)t.ck * GEO::TILEP * sizeof(float);     // two staging buffers
+    static bool big_lds_allowed = false;
+    if (lds_bytes > 64 * 1024 && !big_lds_allowed) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+        big_lds_allowed = true;
+    }
     hipLaunchKernelGGL(tiled_conv_kernel<GEO>, dim3((unsigned)blocks), dim3(64 * waves), lds_bytes,
                        stream, a);
     return hipGetLastError();
@@ -257,7 +288,7 @@ PATDNN_VARIANTS
 
 static const TiledVariant kVariants[] = {
 #define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS)                                        \
-    {#name, G, PR, PC, S, TGX, DENSE, Geo_##name::TILEP, Geo_##name::NB * Geo_##name::BAND, \
+    {#name, G, PR, PC, S, TGX, DENSE, Geo_##name::TILEP, Geo_##name::TILEP, \
      MAXSLOTS, Stream_##name::kBlockBytes, Stream_##name::kEndOff, Stream_##name::kLoadWinOff, \
      Stream_##name::kBatch, &launch_tiled<Geo_##name>},
     PATDNN_VARIANTS

@@ -91,12 +91,12 @@ bool variant_fits_layer(const patdnn_layer* h, const TiledVariant& v)
     return true;
 }
 
-constexpr int kMaxLdsBytes = 64 * 1024;
+constexpr int kMaxLdsBytes = 160 * 1024;      // LDS of one CU; two staging buffers must fit
 constexpr int kMaxWaves = 8;
 
 int default_ck(const TiledVariant& v, int c_in)
 {
-    const int max_ck = kMaxLdsBytes / (4 * v.lds_floats_per_channel);
+    const int max_ck = kMaxLdsBytes / (8 * v.lds_floats_per_channel);
     return std::max(1, std::min(std::min(8, max_ck), c_in));
 }
 
@@ -110,14 +110,14 @@ bool resolve_tiled_params(const patdnn_layer* h, const TiledVariant& v, const Co
     if (min_waves > kMaxWaves) return false;
     if (waves <= 0) waves = std::max(min_waves, std::min(num_groups, 4));
     if (waves < min_waves || waves > kMaxWaves) return false;
-    const int max_ck = kMaxLdsBytes / (4 * v.lds_floats_per_channel);
+    const int max_ck = kMaxLdsBytes / (8 * v.lds_floats_per_channel);
     if (max_ck < 1) return false;
     if (ck <= 0) ck = default_ck(v, s.c_in);
     if (ck < 1 || ck > max_ck) return false;
-    // staging offsets are 32-bit, relative to the first image of a tile
+    // staging offsets are 32-bit byte offsets relative to the first image of a tile
     const int nb = 64 / v.TGX;
     const long long span = (long long)(nb + 1) * s.c_in * s.h * s.w;
-    if (span >= (1ll << 31)) return false;
+    if (span >= (1ll << 30)) return false;
     return true;
 }
 
@@ -412,7 +412,7 @@ patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
         const int min_waves = (v.stage_elems + 64 * v.max_slots - 1) / (64 * v.max_slots);
         if (cfg->waves && cfg->waves < min_waves)
             return fail(PATDNN_EUNSUPPORTED, "too few wavefronts to stage a tile");
-        if (cfg->ck && cfg->ck * 4 * v.lds_floats_per_channel > kMaxLdsBytes)
+        if (cfg->ck && cfg->ck * 8 * v.lds_floats_per_channel > kMaxLdsBytes)
             return fail(PATDNN_EUNSUPPORTED, "ck exceeds the LDS budget");
     }
     h->cfg = *cfg;
