@@ -27,6 +27,7 @@
 //   * Dense (unpruned) layers use the same staging and register tiling with a plain
 //     9-tap loop and no stream.
 #include <type_traits>
+#include <cstdlib>
 
 #include "kernels.hpp"
 #include "layout.hpp"
@@ -43,7 +44,7 @@ struct TiledArgs {
     const float* payload;
     const float* w9;
     int32_t n, c_in, c_out, h, w, ho, wo, pad, relu;
-    int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets;
+    int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets, debug;
 };
 
 template <int G_, int PR_, int PC_, int S_, int TGX_, bool DENSE_, int MAXSLOTS_>
@@ -54,13 +55,13 @@ struct Geo {
     static constexpr int WR = (PR - 1) * S + 3;         // window (= staged band) rows
     static constexpr int WC = (PC - 1) * S + 3;         // window columns per lane
     static constexpr int PITCH = (TGX * PC - 1) * S + 3;  // staged band columns
-    static constexpr int BAND = WR * PITCH;             // staged floats per band
-    // bands start 16 banks apart (mod 64) so that the NB bands of a wavefront do not
-    // collide on LDS banks when every lane reads the same window element
-    static constexpr int BANDP = NB == 1 ? BAND : BAND + ((16 - BAND % 64) + 64) % 64;
-    // LDS floats per staged channel; a multiple of 64 because every staging instruction
-    // of a wavefront fills 64 consecutive dwords
-    static constexpr int TILEP = (NB * BANDP + 63) / 64 * 64;
+    // LDS layout of one staged channel: [window row][band][column] - the same row of
+    // the NB bands side by side, so that 64 consecutive LDS dwords (what one staging
+    // instruction of a wavefront fills) come from a short run of one image row when the
+    // bands are neighbours in x
+    static constexpr int ROWP = NB * PITCH;             // floats per staged row
+    // floats per staged channel; a multiple of 64 (one staging instruction = 64 dwords)
+    static constexpr int TILEP = (WR * ROWP + 63) / 64 * 64;
     static constexpr int NACC = PR * PC;
 };
 
@@ -99,8 +100,14 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     const int nthreads = blockDim.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tile = blockIdx.x / a.fgsets;
-    const int fgset = blockIdx.x - tile * a.fgsets;
+    // Workgroups are handed to the 8 XCDs round-robin by blockIdx; renumber them so that
+    // each XCD works on a contiguous range: the workgroups that stage the same bands
+    // (different filter groups) then share one L2.
+    const int nblk = gridDim.x;
+    const int per_xcd = nblk >> 3, xcd = blockIdx.x & 7, rank = blockIdx.x >> 3;
+    const int bid = rank < per_xcd ? xcd * per_xcd + rank : blockIdx.x;   // tail (< 8 blocks) keeps its id
+    const int tile = bid / a.fgsets;
+    const int fgset = bid - tile * a.fgsets;
     const int group = fgset * a.waves + wave;
     const int band0 = tile * NB;
     const int plane = a.h * a.w;
@@ -117,9 +124,9 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     for (int k = 0; k < GEO::MAXSLOTS; ++k) {
         const int e = tid + k * nthreads;
         voff[k] = ~0u;
-        const int b = e / GEO::BANDP, rem = e - b * GEO::BANDP;
-        if (b < NB && rem < GEO::BAND) {
-            const int q = rem / PITCH, x = rem - q * PITCH;
+        const int q = e / GEO::ROWP, rem = e - q * GEO::ROWP;
+        if (q < WR) {
+            const int b = rem / PITCH, x = rem - b * PITCH;
             const int band = band0 + b;
             if (band < a.num_bands) {
                 const int bxi = band % a.bx, t = band / a.bx;
@@ -137,6 +144,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     const int buf_floats = a.ck * GEO::TILEP;
 
     auto stage = [&](int c0, lds_f32* buf) {
+        if (a.debug & 1) return;
         const int cn = min(a.ck, a.c_in - c0);
         for (int c = 0; c < cn; ++c) {
             const size_t off = (size_t)(c0 + c) * plane * 4;
@@ -166,7 +174,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
         oy0 = byi * PR;
         ox0 = (bxi * TGX + gx) * PC;
     }
-    const int lane_off = lb * GEO::BANDP + gx * PC * S;      // floats, inside one staged channel
+    const int lane_off = lb * PITCH + gx * PC * S;           // floats, inside one staged channel
 
     float acc[G][GEO::NACC];
 #pragma unroll
@@ -194,7 +202,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
 #pragma unroll
                     for (int q = 0; q < WR; ++q)
 #pragma unroll
-                        for (int r = 0; r < WC; ++r) win[q * WC + r] = base[q * PITCH + r];
+                        for (int r = 0; r < WC; ++r) win[q * WC + r] = base[q * GEO::ROWP + r];
                     const float* wp = a.w9 + ((size_t)group * a.c_in + (c0 + c)) * (G * 9);
 #pragma unroll
                     for (int s = 0; s < G; ++s)
@@ -222,7 +230,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     }
 
     // ---- epilogue: bias, ReLU, scatter to the original output channel
-    if (group_ok && band_ok) {
+    if (group_ok && band_ok && !(a.debug & 2)) {
         const size_t oplane = (size_t)a.ho * a.wo;
 #pragma unroll
         for (int s = 0; s < G; ++s) {
@@ -261,6 +269,7 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
     a.num_bands = (int32_t)bands;
     a.ck = t.ck; a.num_chunks = t.num_chunks; a.waves = waves;
     a.fgsets = (t.num_groups + waves - 1) / waves;
+    { const char* d = getenv("PATDNN_DEBUG"); a.debug = d ? atoi(d) : 0; }
     const long long blocks = tiles * a.fgsets;
     if (bands > INT32_MAX || blocks > INT32_MAX) return hipErrorInvalidValue;
     const size_t lds_bytes = 2 * (size_t)t.ck * GEO::TILEP * sizeof(float);     // two staging buffers
