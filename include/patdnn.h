@@ -175,6 +175,46 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
                             int32_t w_in, const float* bias, float* output, void* stream,
                             float* best_us);
 
+/*
+ * The filter-group layout that a tiled sparse variant executes (section 5.2-5.4 as
+ * laid out for this GPU), for inspection and round-trip tests.  `ck` as in
+ * patdnn_config_t (0 = the variant's default).  The layout is built if the handle
+ * does not hold it yet.
+ *   A group is `G` consecutive filters of the reordered layer; `slot_channel` gives
+ *   the original output channel of each (group, slot), -1 for an unused slot.
+ *   Per group and per chunk of `ck` input channels, `chunk_ptr` gives the first
+ *   step; a step is 24 dwords:
+ *     0..15   four weights each of up to `records` kernels that read ONE input channel
+ *     16..19  per kernel: table_off + ((set*G + slot)*56 + pattern index)*block_bytes,
+ *             pattern index = rank of the pattern among the 56 centre-keeping
+ *             four-entry patterns (section 4.1) ordered by their other three
+ *             positions; set = window register set (0, or 0/1 with double_window);
+ *             the entry after the last kernel holds 3*ctrl_bytes or 4*ctrl_bytes
+ *             ("step done" for an even / odd step of the chunk)
+ *     20      what runs when the step starts, k*ctrl_bytes: k = 0 / 1 load a channel's
+ *             window into set 0 / 1, 2 nothing, 5 end of the chunk's stream
+ *     21      byte offset of that channel inside the staged chunk
+ *             (channel index in the chunk * lds_channel_bytes)
+ *   With double_window the window loaded by a step is the one the NEXT channel's
+ *   kernels use, and a chunk's stream opens with a step that only loads.
+ * patdnn_export_tiled copies the arrays to HOST buffers (read back from the device
+ * unless the handle is host-only); any pointer may be NULL.
+ */
+typedef struct {
+    int32_t G, num_groups, ck, num_chunks;
+    int64_t num_steps;             /* steps array holds num_steps*24 dwords */
+    uint32_t block_bytes, table_off, ctrl_bytes, records;
+    int32_t double_window;
+    int32_t lds_channel_bytes;
+} patdnn_tiled_info_t;
+
+patdnn_status_t patdnn_tiled_info(patdnn_handle_t h, int32_t variant, int32_t ck,
+                                  patdnn_tiled_info_t* out);
+patdnn_status_t patdnn_export_tiled(patdnn_handle_t h, int32_t variant, int32_t ck,
+                                    int32_t* slot_channel,   /* [num_groups*G] */
+                                    uint32_t* chunk_ptr,     /* [num_groups*num_chunks] */
+                                    uint32_t* steps);        /* [num_steps*24] */
+
 void        patdnn_destroy(patdnn_handle_t h);          /* NULL is a no-op */
 const char* patdnn_status_string(patdnn_status_t s);
 const char* patdnn_last_error(void);

@@ -24,7 +24,8 @@ PATDNN_VARIANT_FKW = 0
 EXPORTS = [
     "patdnn_encode", "patdnn_conv2d", "patdnn_output_shape", "patdnn_decode",
     "patdnn_export_fkw", "patdnn_layout_stats", "patdnn_num_variants", "patdnn_variant_name",
-    "patdnn_set_config", "patdnn_get_config", "patdnn_tune", "patdnn_destroy",
+    "patdnn_set_config", "patdnn_get_config", "patdnn_tune", "patdnn_tiled_info",
+    "patdnn_export_tiled", "patdnn_destroy",
     "patdnn_status_string", "patdnn_last_error",
 ]
 
@@ -49,6 +50,14 @@ class Stats(ctypes.Structure):
 class Config(ctypes.Structure):
     _fields_ = [("variant", ctypes.c_int32), ("ck", ctypes.c_int32), ("waves", ctypes.c_int32),
                 ("reserved", ctypes.c_int32)]
+
+
+class TiledInfo(ctypes.Structure):
+    _fields_ = [("G", ctypes.c_int32), ("num_groups", ctypes.c_int32), ("ck", ctypes.c_int32),
+                ("num_chunks", ctypes.c_int32), ("num_steps", ctypes.c_int64),
+                ("block_bytes", ctypes.c_uint32), ("table_off", ctypes.c_uint32),
+                ("ctrl_bytes", ctypes.c_uint32), ("records", ctypes.c_uint32),
+                ("double_window", ctypes.c_int32), ("lds_channel_bytes", ctypes.c_int32)]
 
 
 class PatdnnError(RuntimeError):
@@ -81,6 +90,8 @@ def lib() -> ctypes.CDLL:
         L.patdnn_set_config.argtypes = [vp, ctypes.POINTER(Config)]
         L.patdnn_get_config.argtypes = [vp, ctypes.POINTER(Config)]
         L.patdnn_tune.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_float)]
+        L.patdnn_tiled_info.argtypes = [vp, i32, i32, ctypes.POINTER(TiledInfo)]
+        L.patdnn_export_tiled.argtypes = [vp, i32, i32, vp, vp, vp]
         L.patdnn_destroy.argtypes = [vp]
         L.patdnn_destroy.restype = None
         L.patdnn_status_string.argtypes = [i32]
@@ -230,6 +241,24 @@ def patdnn_tune(handle: int, x, bias, out, *, stream=None) -> float:
     return float(best.value)
 
 
+def patdnn_tiled_info(handle: int, variant: int, ck: int = 0) -> dict:
+    t = TiledInfo()
+    _check(lib().patdnn_tiled_info(handle, variant, ck, ctypes.byref(t)))
+    return {k: getattr(t, k) for k, _ in TiledInfo._fields_}
+
+
+def patdnn_export_tiled(handle: int, variant: int, ck: int = 0) -> dict:
+    """The filter-group layout of a tiled sparse variant: info fields plus the arrays."""
+    info = patdnn_tiled_info(handle, variant, ck)
+    out = dict(info)
+    out["slot_channel"] = np.empty((info["num_groups"], info["G"]), np.int32)
+    out["chunk_ptr"] = np.empty((info["num_groups"], info["num_chunks"]), np.uint32)
+    out["steps"] = np.empty((info["num_steps"], 24), np.uint32)
+    _check(lib().patdnn_export_tiled(handle, variant, ck, out["slot_channel"].ctypes.data,
+                                     out["chunk_ptr"].ctypes.data, out["steps"].ctypes.data))
+    return out
+
+
 def patdnn_destroy(handle: Optional[int]) -> None:
     if handle:
         lib().patdnn_destroy(handle)
@@ -276,6 +305,9 @@ class Layer:
 
     def get_config(self):
         return patdnn_get_config(self.handle)
+
+    def export_tiled(self, variant, ck=0):
+        return patdnn_export_tiled(self.handle, variant, ck)
 
     def tune(self, x, bias, out, *, stream=None):
         return patdnn_tune(self.handle, x, bias, out, stream=stream)

@@ -24,15 +24,16 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
 
 
 def sparse_geometries():
-    """(G, PR, PC, S, TGX) of every non-dense X(...) line of variants.def."""
+    """(G, PR, PC, S, TGX, DW) of every non-dense X(...) line of variants.def."""
     geos = set()
     with open(os.path.join(CSRC, "variants.def")) as f:
         for line in f:
             if line.lstrip().startswith("//"):
                 continue
-            m = re.search(r"X\(\s*\w+\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(true|false)", line)
+            m = re.search(r"X\(\s*\w+\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(true|false)"
+                          r"\s*,\s*\d+\s*,\s*(\d+)", line)
             if m and m.group(6) == "false":
-                geos.add(tuple(int(m.group(i)) for i in range(1, 6)))
+                geos.add(tuple(int(m.group(i)) for i in (1, 2, 3, 4, 5, 7)))
     return sorted(geos)
 
 

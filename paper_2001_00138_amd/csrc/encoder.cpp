@@ -199,12 +199,21 @@ void build_tiled(const LayerHost& L, const TiledParams& prm, Tiled& T)
     }
 
     struct Entry { uint32_t chan, upat, slot; int32_t k; };
-    auto push = [&](uint32_t target, float p0, float p1, float p2, float p3) {
-        T.target.push_back(target);
-        const float p[4] = {p0, p1, p2, p3};
-        T.payload.insert(T.payload.end(), p, p + 4);
+    const uint32_t R = prm.records;
+    auto ctrl = [&](int which) { return (uint32_t)which * prm.ctrl_bytes; };
+    auto float_bits = [](float v) { uint32_t u; std::memcpy(&u, &v, 4); return u; };
+    // appends an empty step and returns its index inside the current chunk's stream
+    size_t chunk_first_step = 0;
+    auto new_step = [&](uint32_t window_block, uint32_t window_off) -> uint32_t* {
+        const size_t at = T.steps.size();
+        T.steps.resize(at + kStepDwords, 0u);
+        uint32_t* st = &T.steps[at];
+        const bool odd = ((at / kStepDwords - chunk_first_step) & 1) != 0;   // scalar register set B
+        st[16] = ctrl(odd ? kCtrlDoneB : kCtrlDoneA);
+        st[20] = window_block;
+        st[21] = window_off;
+        return st;
     };
-    auto bits_as_float = [](uint32_t v) { float fl; std::memcpy(&fl, &v, 4); return fl; };
 
     std::vector<Entry> ent;
     for (int g = 0; g < T.num_groups; ++g) {
@@ -234,26 +243,54 @@ void build_tiled(const LayerHost& L, const TiledParams& prm, Tiled& T)
         });
         size_t e = 0;
         for (int chunk = 0; chunk < T.num_chunks; ++chunk) {
-            T.chunk_ptr[(size_t)g * T.num_chunks + chunk] = (uint32_t)T.target.size();
+            chunk_first_step = T.steps.size() / kStepDwords;
+            T.chunk_ptr[(size_t)g * T.num_chunks + chunk] = (uint32_t)chunk_first_step;
             const uint32_t c_end = (uint32_t)std::min(c_in, (chunk + 1) * prm.ck);
-            uint32_t cur = UINT32_MAX;
-            for (; e < ent.size() && ent[e].chan < c_end; ++e) {
-                const Entry& x = ent[e];
-                if (x.chan != cur) {
-                    cur = x.chan;
-                    push(prm.loadwin_off, bits_as_float((cur - (uint32_t)chunk * prm.ck) * prm.channel_bytes),
-                         0.0f, 0.0f, 0.0f);
-                }
-                const float* w = &f.weight[(size_t)x.k * 4];
-                push((x.slot * (uint32_t)kUniverse + x.upat) * prm.block_bytes, w[0], w[1], w[2], w[3]);
+            const size_t e_begin = e;
+            while (e < ent.size() && ent[e].chan < c_end) ++e;
+            // channels of this chunk on which the group has kernels: [begin, end) in ent
+            std::vector<std::pair<size_t, size_t>> runs;
+            for (size_t i = e_begin; i < e;) {
+                size_t j = i;
+                while (j < e && ent[j].chan == ent[i].chan) ++j;
+                runs.emplace_back(i, j);
+                i = j;
             }
-            push(prm.end_off, 0.0f, 0.0f, 0.0f, 0.0f);
+            auto lds_off = [&](size_t run) {
+                return (ent[runs[run].first].chan - (uint32_t)chunk * prm.ck) * prm.channel_bytes;
+            };
+            if (prm.double_window && !runs.empty())
+                new_step(ctrl(kCtrlLoadA), lds_off(0));           // only loads the first window
+            for (size_t r = 0; r < runs.size(); ++r) {
+                const uint32_t set = prm.double_window ? (uint32_t)(r & 1) : 0u;
+                for (size_t i = runs[r].first; i < runs[r].second; i += R) {
+                    uint32_t wblock = ctrl(kCtrlNone), woff = 0;
+                    if (i == runs[r].first) {
+                        if (!prm.double_window) {
+                            wblock = ctrl(kCtrlLoadA);
+                            woff = lds_off(r);
+                        } else if (r + 1 < runs.size()) {
+                            wblock = ctrl(((r + 1) & 1) ? kCtrlLoadB : kCtrlLoadA);
+                            woff = lds_off(r + 1);
+                        }
+                    }
+                    uint32_t* st = new_step(wblock, woff);
+                    const uint32_t done = st[16];
+                    const size_t n = std::min<size_t>(R, runs[r].second - i);
+                    for (size_t q = 0; q < n; ++q) {
+                        const Entry& x = ent[i + q];
+                        const float* w = &f.weight[(size_t)x.k * 4];
+                        for (int t = 0; t < 4; ++t) st[4 * q + t] = float_bits(w[t]);
+                        st[16 + q] = prm.table_off +
+                                     ((set * (uint32_t)G + x.slot) * (uint32_t)kUniverse + x.upat) * prm.block_bytes;
+                    }
+                    if (n < R) st[16 + n] = done;
+                }
+            }
+            new_step(ctrl(kCtrlEnd), 0);
         }
     }
-    if (!L.dense) {
-        // the interpreter requests `batch` records at a time, two requests ahead of use
-        for (uint32_t i = 0; i < 3 * prm.batch; ++i) push(prm.end_off, 0.0f, 0.0f, 0.0f, 0.0f);
-    }
+    if (!L.dense) T.steps.resize(T.steps.size() + kStepDwords, 0u);   // the interpreter fetches one step ahead
 }
 
 }  // namespace patdnn

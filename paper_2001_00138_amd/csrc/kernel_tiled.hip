@@ -40,16 +40,15 @@ struct TiledArgs {
     float* out;
     const int32_t* slot_channel;
     const uint32_t* chunk_ptr;
-    const uint32_t* target;
-    const float* payload;
+    const uint32_t* steps;
     const float* w9;
     int32_t n, c_in, c_out, h, w, ho, wo, pad, relu;
     int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets, debug;
 };
 
-template <int G_, int PR_, int PC_, int S_, int TGX_, bool DENSE_, int MAXSLOTS_>
+template <int G_, int PR_, int PC_, int S_, int TGX_, bool DENSE_, int MAXSLOTS_, int DW_>
 struct Geo {
-    static constexpr int G = G_, PR = PR_, PC = PC_, S = S_, TGX = TGX_, MAXSLOTS = MAXSLOTS_;
+    static constexpr int G = G_, PR = PR_, PC = PC_, S = S_, TGX = TGX_, MAXSLOTS = MAXSLOTS_, DW = DW_;
     static constexpr bool DENSE = DENSE_;
     static constexpr int NB = 64 / TGX;                 // bands per wavefront
     static constexpr int WR = (PR - 1) * S + 3;         // window (= staged band) rows
@@ -65,15 +64,15 @@ struct Geo {
     static constexpr int NACC = PR * PC;
 };
 
-// StreamLoop<G,PR,PC,S,TGX>::run(acc, lane_lds, targets, payload, start): the record
-// interpreter with its table of pattern-specialised FMA blocks (gen_dispatch.py).
-template <int G, int PR, int PC, int S, int TGX>
+// StreamLoop<G,PR,PC,S,TGX,DW>::run(acc, lane_lds, stream): the step interpreter with
+// its table of pattern-specialised FMA blocks (gen_dispatch.py).
+template <int G, int PR, int PC, int S, int TGX, int DW>
 struct StreamLoop;
 
 // dense variants have no stream
-template <int G, int PR, int PC, int S, int TGX>
+template <int G, int PR, int PC, int S, int TGX, int DW>
 struct NoStream {
-    static constexpr unsigned kBlockBytes = 0, kEndOff = 0, kLoadWinOff = 0, kBatch = 0;
+    static constexpr unsigned kBlockBytes = 0, kTableOff = 0, kCtrlBytes = 0, kRecords = 0;
 };
 
 #include "gen/dispatch_all.inc"
@@ -219,12 +218,12 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                         }
                 }
             } else {
-                // the group's records of this chunk: window loads, kernels, end marker
-                const unsigned start = load_uniform(a.chunk_ptr, (size_t)group * a.num_chunks + chunk);
+                // the group's steps of this chunk
+                const unsigned start = (a.debug & 4) ? 0u : load_uniform(a.chunk_ptr, (size_t)group * a.num_chunks + chunk);
                 const unsigned lds_base =
                     (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
-                StreamLoop<G, PR, PC, S, TGX>::run(acc, lds_base + 4u * (unsigned)(cur + lane_off), a.target,
-                                                   a.payload, start);
+                StreamLoop<G, PR, PC, S, TGX, GEO::DW>::run(acc, lds_base + 4u * (unsigned)(cur + lane_off),
+                                                            a.steps + (size_t)start * kStepDwords);
             }
         }
     }
@@ -257,8 +256,8 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
 {
     TiledArgs a{};
     a.in = in; a.bias = bias; a.out = out;
-    a.slot_channel = t.slot_channel; a.chunk_ptr = t.chunk_ptr; a.target = t.target;
-    a.payload = t.payload; a.w9 = t.w9;
+    a.slot_channel = t.slot_channel; a.chunk_ptr = t.chunk_ptr; a.steps = t.steps;
+    a.w9 = t.w9;
     a.n = s.n; a.c_in = s.c_in; a.c_out = s.c_out; a.h = s.h; a.w = s.w; a.ho = s.ho; a.wo = s.wo;
     a.pad = s.pad; a.relu = s.relu;
     a.num_groups = t.num_groups;
@@ -285,21 +284,21 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
     return hipGetLastError();
 }
 
-// X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS) - one line per compiled variant
+// X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, DW) - one line per compiled variant
 #include "variants.def"
 
-#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS)                                        \
-    using Geo_##name = Geo<G, PR, PC, S, TGX, DENSE, MAXSLOTS>;                            \
-    using Stream_##name = std::conditional<DENSE, NoStream<G, PR, PC, S, TGX>,             \
-                                           StreamLoop<G, PR, PC, S, TGX>>::type;
+#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, DW)                                    \
+    using Geo_##name = Geo<G, PR, PC, S, TGX, DENSE, MAXSLOTS, DW>;                        \
+    using Stream_##name = std::conditional<DENSE, NoStream<G, PR, PC, S, TGX, DW>,         \
+                                           StreamLoop<G, PR, PC, S, TGX, DW>>::type;
 PATDNN_VARIANTS
 #undef X
 
 static const TiledVariant kVariants[] = {
-#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS)                                        \
-    {#name, G, PR, PC, S, TGX, DENSE, Geo_##name::TILEP, Geo_##name::TILEP, \
-     MAXSLOTS, Stream_##name::kBlockBytes, Stream_##name::kEndOff, Stream_##name::kLoadWinOff, \
-     Stream_##name::kBatch, &launch_tiled<Geo_##name>},
+#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, DW)                                    \
+    {#name, G, PR, PC, S, TGX, DENSE, DW != 0, Geo_##name::TILEP, Geo_##name::TILEP,       \
+     MAXSLOTS, Stream_##name::kBlockBytes, Stream_##name::kTableOff, Stream_##name::kCtrlBytes, \
+     Stream_##name::kRecords, &launch_tiled<Geo_##name>},
     PATDNN_VARIANTS
 #undef X
 };

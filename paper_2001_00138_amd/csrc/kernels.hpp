@@ -5,6 +5,8 @@
 
 #include <cstdint>
 
+#include "layout.hpp"
+
 namespace patdnn {
 
 struct ConvShape {
@@ -30,9 +32,8 @@ struct DevTiled {
     int32_t ck = 0;            // input channels staged per LDS pass (fixes the chunking of the streams)
     int32_t num_chunks = 0;
     const int32_t* slot_channel = nullptr;
-    const uint32_t* chunk_ptr = nullptr;   // [num_groups][num_chunks] first record of a chunk
-    const uint32_t* target = nullptr;      // [records] byte offset of the record's code block
-    const float* payload = nullptr;        // [records][4]
+    const uint32_t* chunk_ptr = nullptr;   // [num_groups][num_chunks] first step of a chunk
+    const uint32_t* steps = nullptr;       // [steps][kStepDwords]
     const float* w9 = nullptr;
 };
 
@@ -50,14 +51,15 @@ struct TiledVariant {
     int32_t S;        // stride
     int32_t TGX;      // lanes across a band; a wavefront covers 64/TGX bands
     bool dense;       // nine taps, every kernel present
+    bool double_window;   // two sets of window registers: the next channel's window loads early
     int32_t lds_floats_per_channel;   // LDS floats one staged channel takes
     int32_t stage_elems;              // elements staged per channel (without bank padding)
     int32_t max_slots;                // staging elements per thread the kernel can hold
-    // code-table geometry of the record interpreter (sparse variants)
-    uint32_t block_bytes;             // size of one (slot, pattern) block; block i at i*block_bytes
-    uint32_t end_off;                 // offset of the end-of-chunk block
-    uint32_t loadwin_off;             // offset of the window-load block
-    uint32_t batch;                   // records fetched per scalar request
+    // code-table geometry of the step interpreter (sparse variants)
+    uint32_t block_bytes;             // size of one (set, slot, pattern) block
+    uint32_t table_off;               // offset of block 0 from the code base
+    uint32_t ctrl_bytes;              // control block k sits at k*ctrl_bytes
+    uint32_t records;                 // kernels per step
     hipError_t (*launch)(const DevTiled&, const ConvShape&, const float*, const float*, float*,
                          int32_t waves, hipStream_t);
 };

@@ -51,19 +51,31 @@ struct Fkw {
 // ---------------------------------------------------------------------------
 // Tiled layout for one kernel variant.  Filters are taken G at a time from the FKR
 // order, longest first.  Sparse layers: per filter group and per chunk of `ck` input
-// channels, a stream of records that the kernel's interpreter executes in order -
-//   "load window"  target = loadwin_off, payload[0] = byte offset of the channel inside
-//                  the staged chunk (bit pattern of an integer)
-//   "kernel"       target = (slot*56 + universe index) * block_bytes, payload = 4 weights
-//   "end"          target = end_off
+// channels, a sequence of fixed-size steps that the kernel's interpreter executes in
+// order.  One step (kStepDwords = 24 dwords):
+//   dwords  0..15  the four weights of up to `records` (4) kernels, all on ONE input channel
+//   dwords 16..19  per kernel, the byte offset of its code block from the code base:
+//                  table_off + ((window set*G + slot)*56 + universe index) * block_bytes;
+//                  the first unused entry holds the "step done" control block instead
+//   dword  20      control block run when the step starts: "load a window" (into register
+//                  set A or B), "nothing", or "end of the chunk's stream"
+//   dword  21      LDS byte offset, inside the staged chunk, of the channel that block loads
+//   dwords 22..23  zero
 // Kernels are listed channel-major so that one window load serves every kernel of the
 // group on that channel (filter-level load-redundancy elimination, section 5.4), and
-// by pattern inside a channel (kernel reorder, section 5.2).
+// by pattern inside a channel (kernel reorder, section 5.2).  With double window
+// registers the window block of a step loads the NEXT channel's window; the stream
+// then opens with a step that only loads the first one.
 // ---------------------------------------------------------------------------
+constexpr int kStepDwords = 24;
+// control blocks, in code order
+enum { kCtrlLoadA = 0, kCtrlLoadB = 1, kCtrlNone = 2, kCtrlDoneA = 3, kCtrlDoneB = 4, kCtrlEnd = 5 };
+
 struct TiledParams {
     int32_t G = 0;
     int32_t ck = 0;                      // channels per chunk (sparse only)
-    uint32_t block_bytes = 0, end_off = 0, loadwin_off = 0, batch = 0;
+    uint32_t block_bytes = 0, table_off = 0, ctrl_bytes = 0, records = 0;
+    bool double_window = false;
     uint32_t channel_bytes = 0;          // LDS bytes of one staged channel
 };
 
@@ -75,14 +87,13 @@ struct Tiled {
     std::vector<int32_t> slot_channel;   // [num_groups*G] original output channel, -1 = empty slot
     std::vector<int64_t> group_kernels;  // [num_groups] kept kernels per group
     // sparse layers
-    std::vector<uint32_t> chunk_ptr;     // [num_groups][num_chunks]
-    std::vector<uint32_t> target;        // [records + padding]
-    std::vector<float> payload;          // [records + padding][4]
+    std::vector<uint32_t> chunk_ptr;     // [num_groups][num_chunks] first step of the chunk
+    std::vector<uint32_t> steps;         // [steps + 1][kStepDwords] (weights as bit patterns)
     // dense layers
     std::vector<float> w9;               // [num_groups][c_in][G][9]
     size_t bytes() const
     {
-        return 4 * (slot_channel.size() + chunk_ptr.size() + target.size() + payload.size() + w9.size());
+        return 4 * (slot_channel.size() + chunk_ptr.size() + steps.size() + w9.size());
     }
 };
 

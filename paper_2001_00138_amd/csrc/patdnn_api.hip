@@ -134,9 +134,10 @@ patdnn_status_t ensure_tiled(patdnn_layer* h, int vi, int ck, const DevTiled** o
         prm.G = v.G;
         prm.ck = ck;
         prm.block_bytes = v.block_bytes;
-        prm.end_off = v.end_off;
-        prm.loadwin_off = v.loadwin_off;
-        prm.batch = v.batch;
+        prm.table_off = v.table_off;
+        prm.ctrl_bytes = v.ctrl_bytes;
+        prm.records = v.records;
+        prm.double_window = v.double_window;
         prm.channel_bytes = 4u * (uint32_t)v.lds_floats_per_channel;
         build_tiled(h->L, prm, t->host);
         t->dev.G = v.G;
@@ -147,8 +148,7 @@ patdnn_status_t ensure_tiled(patdnn_layer* h, int vi, int ck, const DevTiled** o
             hipError_t e;
             if ((e = upload(h, t->host.slot_channel, &t->dev.slot_channel)) != hipSuccess ||
                 (e = upload(h, t->host.chunk_ptr, &t->dev.chunk_ptr)) != hipSuccess ||
-                (e = upload(h, t->host.target, &t->dev.target)) != hipSuccess ||
-                (e = upload(h, t->host.payload, &t->dev.payload)) != hipSuccess ||
+                (e = upload(h, t->host.steps, &t->dev.steps)) != hipSuccess ||
                 (e = upload(h, t->host.w9, &t->dev.w9)) != hipSuccess)
                 return hip_fail(e, "uploading the tiled layout");
         }
@@ -500,6 +500,68 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
     if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
     h->cfg = best_cfg;
     if (best_us) *best_us = best * 1000.0f;
+    return PATDNN_OK;
+}
+
+static patdnn_status_t find_tiled(patdnn_handle_t h, int32_t variant, int32_t ck, TiledOnDevice** out)
+{
+    if (!h) return fail(PATDNN_EINVAL, "handle is NULL");
+    const int vi = variant - 1;
+    if (vi < 0 || vi >= num_tiled_variants()) return fail(PATDNN_EINVAL, "not a tiled variant");
+    const TiledVariant& v = tiled_variant(vi);
+    if (v.dense || !variant_fits_layer(h, v)) return fail(PATDNN_EUNSUPPORTED, "variant cannot run this layer");
+    if (ck < 0) return fail(PATDNN_EINVAL, "ck out of range");
+    if (ck == 0) ck = default_ck(v, h->L.desc.c_in);
+    ck = std::min(ck, h->L.desc.c_in);
+    if (ck * 8 * v.lds_floats_per_channel > kMaxLdsBytes) return fail(PATDNN_EUNSUPPORTED, "ck exceeds the LDS budget");
+    try {
+        patdnn_status_t st = ensure_tiled(h, vi, ck, nullptr);
+        if (st != PATDNN_OK) return st;
+    } catch (const std::bad_alloc&) {
+        return fail(PATDNN_ENOMEM, "out of host memory");
+    }
+    *out = h->tiled.find(std::make_pair(vi, ck))->second.get();
+    return PATDNN_OK;
+}
+
+patdnn_status_t patdnn_tiled_info(patdnn_handle_t h, int32_t variant, int32_t ck, patdnn_tiled_info_t* out)
+{
+    if (!out) return fail(PATDNN_EINVAL, "out is NULL");
+    TiledOnDevice* t = nullptr;
+    patdnn_status_t st = find_tiled(h, variant, ck, &t);
+    if (st != PATDNN_OK) return st;
+    const TiledVariant& v = tiled_variant(variant - 1);
+    out->G = t->host.G;
+    out->num_groups = t->host.num_groups;
+    out->ck = t->host.ck;
+    out->num_chunks = t->host.num_chunks;
+    out->num_steps = (int64_t)(t->host.steps.size() / kStepDwords);
+    out->block_bytes = v.block_bytes;
+    out->table_off = v.table_off;
+    out->ctrl_bytes = v.ctrl_bytes;
+    out->records = v.records;
+    out->double_window = v.double_window ? 1 : 0;
+    out->lds_channel_bytes = 4 * v.lds_floats_per_channel;
+    return PATDNN_OK;
+}
+
+patdnn_status_t patdnn_export_tiled(patdnn_handle_t h, int32_t variant, int32_t ck,
+                                    int32_t* slot_channel, uint32_t* chunk_ptr, uint32_t* steps)
+{
+    TiledOnDevice* t = nullptr;
+    patdnn_status_t st = find_tiled(h, variant, ck, &t);
+    if (st != PATDNN_OK) return st;
+    auto get = [&](void* dst, const void* dev, const void* host, size_t bytes) -> hipError_t {
+        if (!dst || !bytes) return hipSuccess;
+        if (h->on_device) return hipMemcpy(dst, dev, bytes, hipMemcpyDeviceToHost);
+        std::memcpy(dst, host, bytes);
+        return hipSuccess;
+    };
+    hipError_t e;
+    if ((e = get(slot_channel, t->dev.slot_channel, t->host.slot_channel.data(), t->host.slot_channel.size() * 4)) != hipSuccess ||
+        (e = get(chunk_ptr, t->dev.chunk_ptr, t->host.chunk_ptr.data(), t->host.chunk_ptr.size() * 4)) != hipSuccess ||
+        (e = get(steps, t->dev.steps, t->host.steps.data(), t->host.steps.size() * 4)) != hipSuccess)
+        return hip_fail(e, "reading the tiled layout back");
     return PATDNN_OK;
 }
 

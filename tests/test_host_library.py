@@ -191,3 +191,90 @@ def test_filter_groups_balance_after_reorder():
     assert st["max_group_kernels"] < 1.25 * mean                  # ... groups follow the sort
     assert st["min_group_kernels"] > 0.75 * mean
     L.close()
+
+
+def _walk_steps(t, lib_masks, c_out, c_in):
+    """Executes the step streams of a tiled layout the way the kernel's interpreter does
+    (two alternating scalar register sets, window register sets, one channel per
+    window) and returns the dense weights / ids / mask they describe, plus the number
+    of steps walked.  Raises on anything the interpreter could not execute."""
+    uni = {int(m): i for i, m in enumerate(wl.pattern_universe())}
+    uni_masks = wl.pattern_universe()
+    G, R = t["G"], t["records"]
+    cb, tab, bb = t["ctrl_bytes"], t["table_off"], t["block_bytes"]
+    sets = 2 if t["double_window"] else 1
+    w = np.zeros((c_out, c_in, 3, 3), np.float32)
+    ids = np.full((c_out, c_in), 255, np.int32)
+    km = np.zeros((c_out, c_in), np.uint8)
+    steps = t["steps"]
+    walked = 0
+    for g in range(t["num_groups"]):
+        for chunk in range(t["num_chunks"]):
+            pos = int(t["chunk_ptr"][g, chunk])
+            window = [None] * sets          # channel held by each window register set
+            for k in range(1 << 20):
+                st = steps[pos + k]
+                assert pos + k + 1 < len(steps)         # the step fetched ahead exists
+                walked += 1
+                blk = int(st[20])
+                assert blk % cb == 0 and blk // cb in (0, 1, 2, 5), blk
+                if blk // cb == 5:
+                    break
+                if blk // cb in (0, 1):
+                    assert blk // cb < sets
+                    assert st[21] % t["lds_channel_bytes"] == 0
+                    ch = chunk * t["ck"] + int(st[21]) // t["lds_channel_bytes"]
+                    assert ch < min(c_in, (chunk + 1) * t["ck"])
+                    window[blk // cb] = ch
+                done = (4 if k & 1 else 3) * cb
+                for q in range(R):
+                    tg = int(st[16 + q])
+                    if tg == done:
+                        break
+                    assert tg >= tab and (tg - tab) % bb == 0, tg
+                    idx = (tg - tab) // bb
+                    ws, rest = divmod(idx, G * 56)
+                    slot, u = divmod(rest, 56)
+                    assert ws < sets and window[ws] is not None
+                    # with double windows a set must not be reloaded before its kernels ran:
+                    # the kernels of this step use the set that was loaded one channel ago
+                    if t["double_window"] and blk // cb in (0, 1):
+                        assert ws != blk // cb
+                    co = int(t["slot_channel"][g, slot])
+                    ci = window[ws]
+                    assert co >= 0 and km[co, ci] == 0
+                    km[co, ci] = 1
+                    m = int(uni_masks[u])
+                    where = [p for p in range(9) if (m >> p) & 1]
+                    w[co, ci].reshape(9)[where] = st[4 * q:4 * q + 4].view(np.float32)
+                    hit = [i for i, lm in enumerate(lib_masks) if int(lm) == m]
+                    ids[co, ci] = hit[0]
+            else:
+                raise AssertionError("stream does not end")
+    return w, ids, km, walked
+
+
+@pytest.mark.parametrize("config,layer,ck", [(1, 0, 0), (1, 0, 3), (2, 3, 8), (3, 8, 16), (3, 15, 5)])
+def test_tiled_step_streams_decode_to_the_layer(oracle, config, layer, ck):
+    """Every sparse tiled variant's step stream, interpreted as the kernel does, is exactly
+    the pruned layer: masks, pattern per kernel and weight bits (sections 5.2-5.4)."""
+    d = wl.gen_layer(config, layer, with_input=False)
+    spec = d["spec"]
+    L = _host_layer(d)
+    want = oracle.masked_weights(d["weights"], d["pattern_ids"], d["kernel_mask"], d["pattern_masks"])
+    seen = 0
+    for v in range(1, B.patdnn_num_variants()):
+        try:
+            t = L.export_tiled(v, ck)
+        except B.PatdnnError as e:
+            assert e.status == B.PATDNN_EUNSUPPORTED
+            continue
+        seen += 1
+        w, ids, km, walked = _walk_steps(t, d["pattern_masks"], spec.c_out, spec.c_in)
+        assert w.view(np.uint32).tolist() == want.view(np.uint32).tolist()
+        np.testing.assert_array_equal(km, d["kernel_mask"])
+        np.testing.assert_array_equal(ids[km == 1], d["pattern_ids"][km == 1])
+        assert walked == t["num_steps"] - 1            # every step is reached exactly once (+1 pad)
+        assert sorted(c for c in t["slot_channel"].ravel() if c >= 0) == list(range(spec.c_out))
+    assert seen >= 1
+    L.close()
