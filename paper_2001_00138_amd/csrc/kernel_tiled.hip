@@ -27,7 +27,6 @@
 //   * Dense (unpruned) layers use the same staging and register tiling with a plain
 //     9-tap loop and no stream.
 #include <type_traits>
-#include <cstdlib>
 
 #include "kernels.hpp"
 #include "layout.hpp"
@@ -43,7 +42,7 @@ struct TiledArgs {
     const uint32_t* steps;
     const float* w9;
     int32_t n, c_in, c_out, h, w, ho, wo, pad, relu;
-    int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets, debug;
+    int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets;
 };
 
 template <int G_, int PR_, int PC_, int S_, int TGX_, bool DENSE_, int MAXSLOTS_, int DW_>
@@ -143,7 +142,6 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     const int buf_floats = a.ck * GEO::TILEP;
 
     auto stage = [&](int c0, lds_f32* buf) {
-        if (a.debug & 1) return;
         const int cn = min(a.ck, a.c_in - c0);
         for (int c = 0; c < cn; ++c) {
             const size_t off = (size_t)(c0 + c) * plane * 4;
@@ -219,7 +217,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                 }
             } else {
                 // the group's steps of this chunk
-                const unsigned start = (a.debug & 4) ? 0u : load_uniform(a.chunk_ptr, (size_t)group * a.num_chunks + chunk);
+                const unsigned start = load_uniform(a.chunk_ptr, (size_t)group * a.num_chunks + chunk);
                 const unsigned lds_base =
                     (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
                 StreamLoop<G, PR, PC, S, TGX, GEO::DW>::run(acc, lds_base + 4u * (unsigned)(cur + lane_off),
@@ -229,7 +227,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     }
 
     // ---- epilogue: bias, ReLU, scatter to the original output channel
-    if (group_ok && band_ok && !(a.debug & 2)) {
+    if (group_ok && band_ok) {
         const size_t oplane = (size_t)a.ho * a.wo;
 #pragma unroll
         for (int s = 0; s < G; ++s) {
@@ -268,7 +266,6 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
     a.num_bands = (int32_t)bands;
     a.ck = t.ck; a.num_chunks = t.num_chunks; a.waves = waves;
     a.fgsets = (t.num_groups + waves - 1) / waves;
-    { const char* d = getenv("PATDNN_DEBUG"); a.debug = d ? atoi(d) : 0; }
     const long long blocks = tiles * a.fgsets;
     if (bands > INT32_MAX || blocks > INT32_MAX) return hipErrorInvalidValue;
     const size_t lds_bytes = 2 * (size_t)t.ck * GEO::TILEP * sizeof(float);     // two staging buffers
