@@ -182,21 +182,31 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
  * does not hold it yet.
  *   A group is `G` consecutive filters of the reordered layer; `slot_channel` gives
  *   the original output channel of each (group, slot), -1 for an unused slot.
- *   Per group and per chunk of `ck` input channels, `chunk_ptr` gives the first
- *   step; a step is 24 dwords:
- *     0..15   four weights each of up to `records` kernels that read ONE input channel
- *     16..19  per kernel: table_off + ((set*G + slot)*56 + pattern index)*block_bytes,
- *             pattern index = rank of the pattern among the 56 centre-keeping
- *             four-entry patterns (section 4.1) ordered by their other three
- *             positions; set = window register set (0, or 0/1 with double_window);
- *             the entry after the last kernel holds 3*ctrl_bytes or 4*ctrl_bytes
- *             ("step done" for an even / odd step of the chunk)
+ *   Per group and per chunk of `ck` input channels, the low 28 bits of `chunk_ptr`
+ *   give the first step; a step is 24 dwords and all its kernels read ONE input
+ *   channel.  A kernel's code offset is
+ *     table_off + ((set*G + slot)*56 + pattern index)*block_bytes,
+ *   pattern index = rank of the pattern among the 56 centre-keeping four-entry
+ *   patterns (section 4.1) ordered by their other three positions; set = window
+ *   register set (0, or 0/1 with double_window).
+ *   threaded == 0:
+ *     0..15   four weights each of up to `records` (4) kernels
+ *     16..19  per kernel its code offset; the entry after the last kernel holds
+ *             3*ctrl_bytes or 4*ctrl_bytes ("step done", even / odd step of the chunk)
  *     20      what runs when the step starts, k*ctrl_bytes: k = 0 / 1 load a channel's
  *             window into set 0 / 1, 2 nothing, 5 end of the chunk's stream
  *     21      byte offset of that channel inside the staged chunk
  *             (channel index in the chunk * lds_channel_bytes)
- *   With double_window the window loaded by a step is the one the NEXT channel's
- *   kernels use, and a chunk's stream opens with a step that only loads.
+ *   threaded == 1:
+ *     6i..6i+5  record i < `records` (3): four weights, code offset, zero.  The record
+ *             after the last kernel holds only an offset (after three kernels: dword 22):
+ *             k*ctrl_bytes, the block that enters the NEXT step, k = 3*(step parity) +
+ *             action (0 nothing, 1 / 2 load a window into set 0 / 1), or k = 6, the end
+ *     23      byte offset, inside the staged chunk, of the channel the step's own entry
+ *             block loads
+ *     bits 28..31 of chunk_ptr: k of the block that enters the chunk's first step
+ *   With double_window the window loaded when a step starts is the one the NEXT
+ *   channel's kernels use, and a chunk's stream opens with a step that only loads.
  * patdnn_export_tiled copies the arrays to HOST buffers (read back from the device
  * unless the handle is host-only); any pointer may be NULL.
  */
@@ -206,6 +216,11 @@ typedef struct {
     uint32_t block_bytes, table_off, ctrl_bytes, records;
     int32_t double_window;
     int32_t lds_channel_bytes;
+    int32_t threaded;
+    int32_t patch_rows, patch_cols;   /* output patch of one lane */
+    int32_t conv_stride;
+    int32_t lanes_x;               /* lanes across a band; a wavefront covers 64/lanes_x bands */
+    int32_t experimental;          /* needs PATDNN_EXPERIMENTAL=1 to run */
 } patdnn_tiled_info_t;
 
 patdnn_status_t patdnn_tiled_info(patdnn_handle_t h, int32_t variant, int32_t ck,

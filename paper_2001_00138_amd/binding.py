@@ -57,7 +57,10 @@ class TiledInfo(ctypes.Structure):
                 ("num_chunks", ctypes.c_int32), ("num_steps", ctypes.c_int64),
                 ("block_bytes", ctypes.c_uint32), ("table_off", ctypes.c_uint32),
                 ("ctrl_bytes", ctypes.c_uint32), ("records", ctypes.c_uint32),
-                ("double_window", ctypes.c_int32), ("lds_channel_bytes", ctypes.c_int32)]
+                ("double_window", ctypes.c_int32), ("lds_channel_bytes", ctypes.c_int32),
+                ("threaded", ctypes.c_int32), ("patch_rows", ctypes.c_int32),
+                ("patch_cols", ctypes.c_int32), ("conv_stride", ctypes.c_int32),
+                ("lanes_x", ctypes.c_int32), ("experimental", ctypes.c_int32)]
 
 
 class PatdnnError(RuntimeError):

@@ -24,7 +24,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
 
 
 def sparse_geometries():
-    """(G, PR, PC, S, TGX, DW) of every non-dense X(...) line of variants.def."""
+    """(G, PR, PC, S, TGX, MODE) of every non-dense X(...) line of variants.def."""
     geos = set()
     with open(os.path.join(CSRC, "variants.def")) as f:
         for line in f:

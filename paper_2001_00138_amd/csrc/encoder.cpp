@@ -199,21 +199,13 @@ void build_tiled(const LayerHost& L, const TiledParams& prm, Tiled& T)
     }
 
     struct Entry { uint32_t chan, upat, slot; int32_t k; };
+    // one step before it is laid out: its kernels ([first, last) in `ent`), the window
+    // register set they read, and the window its entry loads (action 0 none, 1 / 2 set 0 / 1)
+    struct Step { size_t first, last; uint32_t set, action, window_off; };
     const uint32_t R = prm.records;
     auto ctrl = [&](int which) { return (uint32_t)which * prm.ctrl_bytes; };
     auto float_bits = [](float v) { uint32_t u; std::memcpy(&u, &v, 4); return u; };
-    // appends an empty step and returns its index inside the current chunk's stream
-    size_t chunk_first_step = 0;
-    auto new_step = [&](uint32_t window_block, uint32_t window_off) -> uint32_t* {
-        const size_t at = T.steps.size();
-        T.steps.resize(at + kStepDwords, 0u);
-        uint32_t* st = &T.steps[at];
-        const bool odd = ((at / kStepDwords - chunk_first_step) & 1) != 0;   // scalar register set B
-        st[16] = ctrl(odd ? kCtrlDoneB : kCtrlDoneA);
-        st[20] = window_block;
-        st[21] = window_off;
-        return st;
-    };
+    std::vector<Step> plan;
 
     std::vector<Entry> ent;
     for (int g = 0; g < T.num_groups; ++g) {
@@ -243,8 +235,6 @@ void build_tiled(const LayerHost& L, const TiledParams& prm, Tiled& T)
         });
         size_t e = 0;
         for (int chunk = 0; chunk < T.num_chunks; ++chunk) {
-            chunk_first_step = T.steps.size() / kStepDwords;
-            T.chunk_ptr[(size_t)g * T.num_chunks + chunk] = (uint32_t)chunk_first_step;
             const uint32_t c_end = (uint32_t)std::min(c_in, (chunk + 1) * prm.ck);
             const size_t e_begin = e;
             while (e < ent.size() && ent[e].chan < c_end) ++e;
@@ -259,38 +249,81 @@ void build_tiled(const LayerHost& L, const TiledParams& prm, Tiled& T)
             auto lds_off = [&](size_t run) {
                 return (ent[runs[run].first].chan - (uint32_t)chunk * prm.ck) * prm.channel_bytes;
             };
+            // ---- the steps of this chunk, independent of how they are dispatched
+            plan.clear();
             if (prm.double_window && !runs.empty())
-                new_step(ctrl(kCtrlLoadA), lds_off(0));           // only loads the first window
+                plan.push_back({0, 0, 0u, 1u, lds_off(0)});          // only loads the first window
             for (size_t r = 0; r < runs.size(); ++r) {
                 const uint32_t set = prm.double_window ? (uint32_t)(r & 1) : 0u;
                 for (size_t i = runs[r].first; i < runs[r].second; i += R) {
-                    uint32_t wblock = ctrl(kCtrlNone), woff = 0;
+                    Step st{i, std::min(i + R, runs[r].second), set, 0u, 0u};
                     if (i == runs[r].first) {
                         if (!prm.double_window) {
-                            wblock = ctrl(kCtrlLoadA);
-                            woff = lds_off(r);
+                            st.action = 1;
+                            st.window_off = lds_off(r);
                         } else if (r + 1 < runs.size()) {
-                            wblock = ctrl(((r + 1) & 1) ? kCtrlLoadB : kCtrlLoadA);
-                            woff = lds_off(r + 1);
+                            st.action = 1 + (uint32_t)((r + 1) & 1);
+                            st.window_off = lds_off(r + 1);
                         }
                     }
-                    uint32_t* st = new_step(wblock, woff);
-                    const uint32_t done = st[16];
-                    const size_t n = std::min<size_t>(R, runs[r].second - i);
-                    for (size_t q = 0; q < n; ++q) {
-                        const Entry& x = ent[i + q];
-                        const float* w = &f.weight[(size_t)x.k * 4];
-                        for (int t = 0; t < 4; ++t) st[4 * q + t] = float_bits(w[t]);
-                        st[16 + q] = prm.table_off +
-                                     ((set * (uint32_t)G + x.slot) * (uint32_t)kUniverse + x.upat) * prm.block_bytes;
-                    }
-                    if (n < R) st[16 + n] = done;
+                    plan.push_back(st);
                 }
             }
-            new_step(ctrl(kCtrlEnd), 0);
+            // ---- lay them out
+            const size_t first_step = T.steps.size() / kStepDwords;
+            if (first_step > kChunkStepMask) { T.steps.clear(); T.overflow = true; return; }
+            auto block_of = [&](const Step& st, const Entry& x) {
+                return prm.table_off +
+                       ((st.set * (uint32_t)G + x.slot) * (uint32_t)kUniverse + x.upat) * prm.block_bytes;
+            };
+            if (!prm.threaded) {
+                T.chunk_ptr[(size_t)g * T.num_chunks + chunk] = (uint32_t)first_step;
+                for (size_t k = 0; k <= plan.size(); ++k) {
+                    const size_t at = T.steps.size();
+                    T.steps.resize(at + kStepDwords, 0u);
+                    uint32_t* d = &T.steps[at];
+                    const uint32_t done = ctrl((k & 1) ? kCtrlDoneB : kCtrlDoneA);   // odd steps: register set B
+                    d[16] = done;
+                    if (k == plan.size()) { d[20] = ctrl(kCtrlEnd); break; }
+                    const Step& st = plan[k];
+                    d[20] = ctrl(st.action == 0 ? kCtrlNone : st.action == 1 ? kCtrlLoadA : kCtrlLoadB);
+                    d[21] = st.window_off;
+                    const size_t n = st.last - st.first;
+                    for (size_t q = 0; q < n; ++q) {
+                        const Entry& x = ent[st.first + q];
+                        const float* w = &f.weight[(size_t)x.k * 4];
+                        for (int t = 0; t < 4; ++t) d[4 * q + t] = float_bits(w[t]);
+                        d[16 + q] = block_of(st, x);
+                    }
+                    if (n < R) d[16 + n] = done;
+                }
+            } else {
+                auto enter = [&](size_t k) {        // control block that enters step k of the chunk
+                    return k == plan.size() ? (uint32_t)kThreadedEnd
+                                            : (uint32_t)(3 * (k & 1)) + plan[k].action;
+                };
+                T.chunk_ptr[(size_t)g * T.num_chunks + chunk] =
+                    (uint32_t)first_step | (enter(0) << kChunkEntryShift);
+                for (size_t k = 0; k < plan.size(); ++k) {
+                    const size_t at = T.steps.size();
+                    T.steps.resize(at + kStepDwords, 0u);
+                    uint32_t* d = &T.steps[at];
+                    const Step& st = plan[k];
+                    d[kThreadedWoff] = st.window_off;
+                    const size_t n = st.last - st.first;
+                    for (size_t q = 0; q < n; ++q) {
+                        const Entry& x = ent[st.first + q];
+                        const float* w = &f.weight[(size_t)x.k * 4];
+                        for (int t = 0; t < 4; ++t) d[kThreadedRecDwords * q + t] = float_bits(w[t]);
+                        d[kThreadedRecDwords * q + 4] = block_of(st, x);
+                    }
+                    d[n < R ? kThreadedRecDwords * n + 4 : (size_t)kThreadedTermFull] = ctrl((int)enter(k + 1));
+                }
+            }
         }
     }
-    if (!L.dense) T.steps.resize(T.steps.size() + kStepDwords, 0u);   // the interpreter fetches one step ahead
+    // the interpreter fetches one step beyond the last one it runs
+    if (!L.dense) T.steps.resize(T.steps.size() + kStepDwords, 0u);
 }
 
 }  // namespace patdnn

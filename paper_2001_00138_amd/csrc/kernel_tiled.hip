@@ -45,9 +45,9 @@ struct TiledArgs {
     int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets;
 };
 
-template <int G_, int PR_, int PC_, int S_, int TGX_, bool DENSE_, int MAXSLOTS_, int DW_>
+template <int G_, int PR_, int PC_, int S_, int TGX_, bool DENSE_, int MAXSLOTS_, int MODE_>
 struct Geo {
-    static constexpr int G = G_, PR = PR_, PC = PC_, S = S_, TGX = TGX_, MAXSLOTS = MAXSLOTS_, DW = DW_;
+    static constexpr int G = G_, PR = PR_, PC = PC_, S = S_, TGX = TGX_, MAXSLOTS = MAXSLOTS_, MODE = MODE_;
     static constexpr bool DENSE = DENSE_;
     static constexpr int NB = 64 / TGX;                 // bands per wavefront
     static constexpr int WR = (PR - 1) * S + 3;         // window (= staged band) rows
@@ -63,13 +63,13 @@ struct Geo {
     static constexpr int NACC = PR * PC;
 };
 
-// StreamLoop<G,PR,PC,S,TGX,DW>::run(acc, lane_lds, stream): the step interpreter with
-// its table of pattern-specialised FMA blocks (gen_dispatch.py).
-template <int G, int PR, int PC, int S, int TGX, int DW>
+// StreamLoop<G,PR,PC,S,TGX,MODE>::run(acc, lane_lds, stream, entry): the step interpreter
+// with its table of pattern-specialised FMA blocks (gen_dispatch.py).
+template <int G, int PR, int PC, int S, int TGX, int MODE>
 struct StreamLoop;
 
 // dense variants have no stream
-template <int G, int PR, int PC, int S, int TGX, int DW>
+template <int G, int PR, int PC, int S, int TGX, int MODE>
 struct NoStream {
     static constexpr unsigned kBlockBytes = 0, kTableOff = 0, kCtrlBytes = 0, kRecords = 0;
 };
@@ -216,12 +216,15 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                         }
                 }
             } else {
-                // the group's steps of this chunk
-                const unsigned start = load_uniform(a.chunk_ptr, (size_t)group * a.num_chunks + chunk);
+                // the group's steps of this chunk: first step, and (threaded dispatch) the
+                // control block that enters it
+                const unsigned cp = load_uniform(a.chunk_ptr, (size_t)group * a.num_chunks + chunk);
+                const unsigned start = cp & kChunkStepMask;
+                using Loop = StreamLoop<G, PR, PC, S, TGX, GEO::MODE>;
                 const unsigned lds_base =
                     (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
-                StreamLoop<G, PR, PC, S, TGX, GEO::DW>::run(acc, lds_base + 4u * (unsigned)(cur + lane_off),
-                                                            a.steps + (size_t)start * kStepDwords);
+                Loop::run(acc, lds_base + 4u * (unsigned)(cur + lane_off),
+                          a.steps + (size_t)start * kStepDwords, (cp >> kChunkEntryShift) * Loop::kCtrlBytes);
             }
         }
     }
@@ -281,19 +284,20 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
     return hipGetLastError();
 }
 
-// X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, DW) - one line per compiled variant
+// X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, MODE, EXPERIMENTAL) - one line per compiled variant
 #include "variants.def"
 
-#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, DW)                                    \
-    using Geo_##name = Geo<G, PR, PC, S, TGX, DENSE, MAXSLOTS, DW>;                        \
-    using Stream_##name = std::conditional<DENSE, NoStream<G, PR, PC, S, TGX, DW>,         \
-                                           StreamLoop<G, PR, PC, S, TGX, DW>>::type;
+#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, MODE, EXPERIMENTAL)                    \
+    using Geo_##name = Geo<G, PR, PC, S, TGX, DENSE, MAXSLOTS, MODE>;                      \
+    using Stream_##name = std::conditional<DENSE, NoStream<G, PR, PC, S, TGX, MODE>,       \
+                                           StreamLoop<G, PR, PC, S, TGX, MODE>>::type;
 PATDNN_VARIANTS
 #undef X
 
 static const TiledVariant kVariants[] = {
-#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, DW)                                    \
-    {#name, G, PR, PC, S, TGX, DENSE, DW != 0, Geo_##name::TILEP, Geo_##name::TILEP,       \
+#define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, MODE, EXPERIMENTAL)                    \
+    {#name, G, PR, PC, S, TGX, DENSE, ((MODE) & 1) != 0, ((MODE) & 2) != 0, EXPERIMENTAL != 0, \
+     Geo_##name::TILEP, Geo_##name::TILEP,                                                 \
      MAXSLOTS, Stream_##name::kBlockBytes, Stream_##name::kTableOff, Stream_##name::kCtrlBytes, \
      Stream_##name::kRecords, &launch_tiled<Geo_##name>},
     PATDNN_VARIANTS

@@ -32,7 +32,7 @@ struct DevTiled {
     int32_t ck = 0;            // input channels staged per LDS pass (fixes the chunking of the streams)
     int32_t num_chunks = 0;
     const int32_t* slot_channel = nullptr;
-    const uint32_t* chunk_ptr = nullptr;   // [num_groups][num_chunks] first step of a chunk
+    const uint32_t* chunk_ptr = nullptr;   // [num_groups][num_chunks] first step of a chunk | entry block << 28
     const uint32_t* steps = nullptr;       // [steps][kStepDwords]
     const float* w9 = nullptr;
 };
@@ -52,6 +52,8 @@ struct TiledVariant {
     int32_t TGX;      // lanes across a band; a wavefront covers 64/TGX bands
     bool dense;       // nine taps, every kernel present
     bool double_window;   // two sets of window registers: the next channel's window loads early
+    bool threaded;        // every code block jumps straight to the next kernel's block
+    bool experimental;    // not yet measured on hardware: never chosen by default or by the tuner
     int32_t lds_floats_per_channel;   // LDS floats one staged channel takes
     int32_t stage_elems;              // elements staged per channel (without bank padding)
     int32_t max_slots;                // staging elements per thread the kernel can hold

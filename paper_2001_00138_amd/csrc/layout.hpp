@@ -51,31 +51,49 @@ struct Fkw {
 // ---------------------------------------------------------------------------
 // Tiled layout for one kernel variant.  Filters are taken G at a time from the FKR
 // order, longest first.  Sparse layers: per filter group and per chunk of `ck` input
-// channels, a sequence of fixed-size steps that the kernel's interpreter executes in
-// order.  One step (kStepDwords = 24 dwords):
-//   dwords  0..15  the four weights of up to `records` (4) kernels, all on ONE input channel
-//   dwords 16..19  per kernel, the byte offset of its code block from the code base:
-//                  table_off + ((window set*G + slot)*56 + universe index) * block_bytes;
-//                  the first unused entry holds the "step done" control block instead
-//   dword  20      control block run when the step starts: "load a window" (into register
-//                  set A or B), "nothing", or "end of the chunk's stream"
-//   dword  21      LDS byte offset, inside the staged chunk, of the channel that block loads
-//   dwords 22..23  zero
+// channels, a sequence of fixed-size steps (kStepDwords = 24 dwords) that the kernel's
+// interpreter executes in order.  All kernels of a step read ONE input channel.
 // Kernels are listed channel-major so that one window load serves every kernel of the
 // group on that channel (filter-level load-redundancy elimination, section 5.4), and
-// by pattern inside a channel (kernel reorder, section 5.2).  With double window
-// registers the window block of a step loads the NEXT channel's window; the stream
-// then opens with a step that only loads the first one.
+// by pattern inside a channel (kernel reorder, section 5.2).  A kernel's code block
+// sits at table_off + ((window set*G + slot)*56 + universe index) * block_bytes from
+// the code base; control block k at k * ctrl_bytes.
+//
+// Call dispatch, one step:
+//   dwords  0..15  the four weights of up to 4 kernels
+//   dwords 16..19  per kernel, the offset of its code block; the first unused entry
+//                  holds the "step done" control block (kCtrlDoneA / B for an even / odd
+//                  step of the chunk)
+//   dword  20      control block run when the step starts: load a window into register
+//                  set A or B, nothing, or the end of the chunk's stream
+//   dword  21      LDS byte offset, inside the staged chunk, of the channel that block loads
+//   dwords 22..23  zero
+// Threaded dispatch, one step:
+//   dwords 6i..6i+5 (i = 0..2)  record i: four weights, offset of its code block, zero
+//   The record after the last kernel holds only an offset: the control block that enters
+//   the NEXT step (3*set + action: set = 0 / 1 for an even / odd step of the chunk,
+//   action 0 nothing, 1 / 2 load a window into register set 0 / 1), or kThreadedEnd.
+//   After three kernels that offset is dword 22.
+//   dword  23      LDS byte offset of the channel whose window the step's OWN entry block loads
+//   The control block that enters the first step of a chunk is stored beside the chunk's
+//   first-step index (bits 28..31 of chunk_ptr).
+// With two sets of window registers the window loaded when a step starts is the one the
+// NEXT channel's kernels use; the stream then opens with a step that only loads the first.
 // ---------------------------------------------------------------------------
 constexpr int kStepDwords = 24;
-// control blocks, in code order
+// control blocks of call dispatch, in code order
 enum { kCtrlLoadA = 0, kCtrlLoadB = 1, kCtrlNone = 2, kCtrlDoneA = 3, kCtrlDoneB = 4, kCtrlEnd = 5 };
+// threaded dispatch
+constexpr int kThreadedEnd = 6, kThreadedRecDwords = 6, kThreadedTermFull = 22, kThreadedWoff = 23;
+// chunk_ptr packing
+constexpr uint32_t kChunkStepMask = 0x0FFFFFFFu;
+constexpr int kChunkEntryShift = 28;
 
 struct TiledParams {
     int32_t G = 0;
     int32_t ck = 0;                      // channels per chunk (sparse only)
     uint32_t block_bytes = 0, table_off = 0, ctrl_bytes = 0, records = 0;
-    bool double_window = false;
+    bool double_window = false, threaded = false;
     uint32_t channel_bytes = 0;          // LDS bytes of one staged channel
 };
 
@@ -84,10 +102,11 @@ struct Tiled {
     int32_t num_groups = 0;
     int32_t ck = 0, num_chunks = 0;
     bool dense = false;
+    bool overflow = false;               // more steps than chunk_ptr can address
     std::vector<int32_t> slot_channel;   // [num_groups*G] original output channel, -1 = empty slot
     std::vector<int64_t> group_kernels;  // [num_groups] kept kernels per group
     // sparse layers
-    std::vector<uint32_t> chunk_ptr;     // [num_groups][num_chunks] first step of the chunk
+    std::vector<uint32_t> chunk_ptr;     // [num_groups][num_chunks] first step of the chunk | entry block << 28
     std::vector<uint32_t> steps;         // [steps + 1][kStepDwords] (weights as bit patterns)
     // dense layers
     std::vector<float> w9;               // [num_groups][c_in][G][9]

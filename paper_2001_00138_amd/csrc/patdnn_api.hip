@@ -4,6 +4,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <memory>
@@ -91,6 +92,20 @@ bool variant_fits_layer(const patdnn_layer* h, const TiledVariant& v)
     return true;
 }
 
+// Variants marked experimental have passed the host model of the interpreter but have not
+// been measured on hardware; they run only when the caller asks for them by number AND the
+// environment carries PATDNN_EXPERIMENTAL=1.
+bool experimental_allowed()
+{
+    const char* e = std::getenv("PATDNN_EXPERIMENTAL");
+    return e && e[0] == '1' && e[1] == 0;
+}
+
+bool variant_selectable(const patdnn_layer* h, const TiledVariant& v)
+{
+    return variant_fits_layer(h, v) && !v.experimental;
+}
+
 constexpr int kMaxLdsBytes = 160 * 1024;      // LDS of one CU; two staging buffers must fit
 constexpr int kMaxWaves = 8;
 
@@ -138,8 +153,10 @@ patdnn_status_t ensure_tiled(patdnn_layer* h, int vi, int ck, const DevTiled** o
         prm.ctrl_bytes = v.ctrl_bytes;
         prm.records = v.records;
         prm.double_window = v.double_window;
+        prm.threaded = v.threaded;
         prm.channel_bytes = 4u * (uint32_t)v.lds_floats_per_channel;
         build_tiled(h->L, prm, t->host);
+        if (t->host.overflow) return fail(PATDNN_EUNSUPPORTED, "layer has too many steps for this variant");
         t->dev.G = v.G;
         t->dev.num_groups = t->host.num_groups;
         t->dev.ck = ck;
@@ -187,6 +204,8 @@ patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const Conv
     if (vi < 0 || vi >= num_tiled_variants()) return fail(PATDNN_EINVAL, "no such variant");
     const TiledVariant& v = tiled_variant(vi);
     if (!variant_fits_layer(h, v)) return fail(PATDNN_EUNSUPPORTED, "variant cannot run this layer");
+    if (v.experimental && !experimental_allowed())
+        return fail(PATDNN_EUNSUPPORTED, "experimental variant: set PATDNN_EXPERIMENTAL=1 to run it");
     int32_t ck = c.ck, waves = c.waves;
     if (!resolve_tiled_params(h, v, s, ck, waves))
         return fail(PATDNN_EUNSUPPORTED, "launch parameters outside the variant's limits");
@@ -207,7 +226,7 @@ patdnn_config_t default_config(patdnn_layer* h, const ConvShape& s)
 {
     for (int vi = 0; vi < num_tiled_variants(); ++vi) {
         const TiledVariant& v = tiled_variant(vi);
-        if (!variant_fits_layer(h, v)) continue;
+        if (!variant_selectable(h, v)) continue;
         int32_t ck = 0, waves = 0;
         if (resolve_tiled_params(h, v, s, ck, waves)) return patdnn_config_t{vi + 1, ck, waves, 0};
     }
@@ -253,7 +272,7 @@ patdnn_status_t patdnn_encode(const patdnn_layer_desc_t* desc, const float* dens
     // build (and upload) the group layouts of every tiled variant that can run the layer
     try {
         for (int vi = 0; vi < num_tiled_variants(); ++vi)
-            if (variant_fits_layer(h.get(), tiled_variant(vi))) {
+            if (variant_selectable(h.get(), tiled_variant(vi))) {
                 st = ensure_tiled(h.get(), vi, default_ck(tiled_variant(vi), desc->c_in), nullptr);
                 if (st != PATDNN_OK) return st;
             }
@@ -407,6 +426,8 @@ patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
     if (cfg->variant > 0) {
         const TiledVariant& v = tiled_variant(cfg->variant - 1);
         if (!variant_fits_layer(h, v)) return fail(PATDNN_EUNSUPPORTED, "variant cannot run this layer");
+        if (v.experimental && h->on_device && !experimental_allowed())
+            return fail(PATDNN_EUNSUPPORTED, "experimental variant: set PATDNN_EXPERIMENTAL=1 to run it");
         if (cfg->ck < 0 || cfg->waves < 0 || cfg->waves > kMaxWaves)
             return fail(PATDNN_EINVAL, "ck / waves out of range");
         const int min_waves = (v.stage_elems + 64 * v.max_slots - 1) / (64 * v.max_slots);
@@ -454,7 +475,7 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
     const int wave_opts[] = {1, 2, 4, 8};
     for (int vi = 0; vi < num_tiled_variants(); ++vi) {
         const TiledVariant& v = tiled_variant(vi);
-        if (!variant_fits_layer(h, v)) continue;
+        if (!variant_selectable(h, v)) continue;
         const int groups = (s.c_out + v.G - 1) / v.G;
         for (int ck : ck_opts)
             for (int waves : wave_opts) {
@@ -542,6 +563,12 @@ patdnn_status_t patdnn_tiled_info(patdnn_handle_t h, int32_t variant, int32_t ck
     out->records = v.records;
     out->double_window = v.double_window ? 1 : 0;
     out->lds_channel_bytes = 4 * v.lds_floats_per_channel;
+    out->threaded = v.threaded ? 1 : 0;
+    out->patch_rows = v.PR;
+    out->patch_cols = v.PC;
+    out->conv_stride = v.S;
+    out->lanes_x = v.TGX;
+    out->experimental = v.experimental ? 1 : 0;
     return PATDNN_OK;
 }
 

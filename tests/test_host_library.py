@@ -196,61 +196,91 @@ def test_filter_groups_balance_after_reorder():
 def _walk_steps(t, lib_masks, c_out, c_in):
     """Executes the step streams of a tiled layout the way the kernel's interpreter does
     (two alternating scalar register sets, window register sets, one channel per
-    window) and returns the dense weights / ids / mask they describe, plus the number
-    of steps walked.  Raises on anything the interpreter could not execute."""
-    uni = {int(m): i for i, m in enumerate(wl.pattern_universe())}
+    window, call or threaded dispatch) and returns the dense weights / ids / mask they
+    describe, plus the number of steps walked.  Raises on anything the interpreter
+    could not execute."""
     uni_masks = wl.pattern_universe()
     G, R = t["G"], t["records"]
     cb, tab, bb = t["ctrl_bytes"], t["table_off"], t["block_bytes"]
     sets = 2 if t["double_window"] else 1
+    threaded = bool(t["threaded"])
     w = np.zeros((c_out, c_in, 3, 3), np.float32)
     ids = np.full((c_out, c_in), 255, np.int32)
     km = np.zeros((c_out, c_in), np.uint8)
     steps = t["steps"]
     walked = 0
+
+    def load_window(window, which, off, chunk):
+        assert which < sets
+        assert off % t["lds_channel_bytes"] == 0
+        ch = chunk * t["ck"] + off // t["lds_channel_bytes"]
+        assert ch < min(c_in, (chunk + 1) * t["ck"])
+        window[which] = ch
+
+    def run_kernel(g, window, tg, weights, loading):
+        assert tg >= tab and (tg - tab) % bb == 0, tg
+        ws, rest = divmod((tg - tab) // bb, G * 56)
+        slot, u = divmod(rest, 56)
+        assert ws < sets and window[ws] is not None
+        # with two window sets, the set being loaded is not the one the kernels read
+        if t["double_window"] and loading is not None:
+            assert ws != loading
+        co, ci = int(t["slot_channel"][g, slot]), window[ws]
+        assert co >= 0 and km[co, ci] == 0
+        km[co, ci] = 1
+        m = int(uni_masks[u])
+        w[co, ci].reshape(9)[[p for p in range(9) if (m >> p) & 1]] = weights.view(np.float32)
+        ids[co, ci] = [i for i, lm in enumerate(lib_masks) if int(lm) == m][0]
+
     for g in range(t["num_groups"]):
         for chunk in range(t["num_chunks"]):
-            pos = int(t["chunk_ptr"][g, chunk])
+            cp = int(t["chunk_ptr"][g, chunk])
+            pos, entry = cp & 0x0FFFFFFF, cp >> 28
             window = [None] * sets          # channel held by each window register set
-            for k in range(1 << 20):
-                st = steps[pos + k]
-                assert pos + k + 1 < len(steps)         # the step fetched ahead exists
-                walked += 1
-                blk = int(st[20])
-                assert blk % cb == 0 and blk // cb in (0, 1, 2, 5), blk
-                if blk // cb == 5:
-                    break
-                if blk // cb in (0, 1):
-                    assert blk // cb < sets
-                    assert st[21] % t["lds_channel_bytes"] == 0
-                    ch = chunk * t["ck"] + int(st[21]) // t["lds_channel_bytes"]
-                    assert ch < min(c_in, (chunk + 1) * t["ck"])
-                    window[blk // cb] = ch
-                done = (4 if k & 1 else 3) * cb
-                for q in range(R):
-                    tg = int(st[16 + q])
-                    if tg == done:
+            if not threaded:
+                assert entry == 0
+                for k in range(1 << 20):
+                    st = steps[pos + k]
+                    assert pos + k + 1 < len(steps)         # the step fetched ahead exists
+                    walked += 1
+                    blk = int(st[20])
+                    assert blk % cb == 0 and blk // cb in (0, 1, 2, 5), blk
+                    if blk // cb == 5:
                         break
-                    assert tg >= tab and (tg - tab) % bb == 0, tg
-                    idx = (tg - tab) // bb
-                    ws, rest = divmod(idx, G * 56)
-                    slot, u = divmod(rest, 56)
-                    assert ws < sets and window[ws] is not None
-                    # with double windows a set must not be reloaded before its kernels ran:
-                    # the kernels of this step use the set that was loaded one channel ago
-                    if t["double_window"] and blk // cb in (0, 1):
-                        assert ws != blk // cb
-                    co = int(t["slot_channel"][g, slot])
-                    ci = window[ws]
-                    assert co >= 0 and km[co, ci] == 0
-                    km[co, ci] = 1
-                    m = int(uni_masks[u])
-                    where = [p for p in range(9) if (m >> p) & 1]
-                    w[co, ci].reshape(9)[where] = st[4 * q:4 * q + 4].view(np.float32)
-                    hit = [i for i, lm in enumerate(lib_masks) if int(lm) == m]
-                    ids[co, ci] = hit[0]
+                    loading = blk // cb if blk // cb in (0, 1) else None
+                    if loading is not None:
+                        load_window(window, loading, int(st[21]), chunk)
+                    done = (4 if k & 1 else 3) * cb
+                    for q in range(R):
+                        if int(st[16 + q]) == done:
+                            break
+                        run_kernel(g, window, int(st[16 + q]), st[4 * q:4 * q + 4], loading)
+                else:
+                    raise AssertionError("stream does not end")
             else:
-                raise AssertionError("stream does not end")
+                k = 0
+                while True:
+                    assert entry <= 6 and k < (1 << 20)
+                    if entry == 6:
+                        break
+                    st = steps[pos + k]
+                    assert pos + k + 1 < len(steps)
+                    walked += 1
+                    assert entry // 3 == (k & 1)            # the register set the step was fetched into
+                    loading = entry % 3 - 1 if entry % 3 else None
+                    if loading is not None:
+                        load_window(window, loading, int(st[23]), chunk)
+                    q = 0
+                    while True:
+                        tg = int(st[6 * q + 4]) if q < R else int(st[22])
+                        if tg < tab:                        # a control block: the step is over
+                            assert tg % cb == 0
+                            entry = tg // cb
+                            break
+                        assert q < R
+                        run_kernel(g, window, tg, st[6 * q:6 * q + 4], loading)
+                        q += 1
+                    k += 1
     return w, ids, km, walked
 
 
@@ -275,6 +305,7 @@ def test_tiled_step_streams_decode_to_the_layer(oracle, config, layer, ck):
         np.testing.assert_array_equal(km, d["kernel_mask"])
         np.testing.assert_array_equal(ids[km == 1], d["pattern_ids"][km == 1])
         assert walked == t["num_steps"] - 1            # every step is reached exactly once (+1 pad)
+        assert t["threaded"] in (0, 1) and t["records"] == (3 if t["threaded"] else 4)
         assert sorted(c for c in t["slot_channel"].ravel() if c >= 0) == list(range(spec.c_out))
-    assert seen >= 1
+    assert seen >= 4          # call / threaded dispatch x one / two window register sets
     L.close()
