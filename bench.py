@@ -41,6 +41,7 @@ def main() -> int:
     ap.add_argument("--no-tune", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-compare", action="store_true")
+    ap.add_argument("--no-latency", action="store_true", help="skip the batch-1 stack latency leg")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -59,6 +60,10 @@ def main() -> int:
     B.lib()
     torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
+
+    def variant_name(cfg):
+        # variant -1: the library picks its default configuration at every call
+        return B.patdnn_variant_name(cfg["variant"]) if cfg["variant"] >= 0 else "auto"
 
     # ------------------------------------------------------------------ set-up
     specs = wl.config_layers(args.config)
@@ -81,7 +86,7 @@ def main() -> int:
                            nz=wl.nz_flops(spec, kept), dense_eq=wl.dense_flops(spec),
                            bytes=wl.algorithmic_bytes(spec, kept)))
         _log(f"[setup] {spec.name}: {spec.c_in}->{spec.c_out} @{spec.h} N={spec.n} kept={kept} "
-             f"cfg={cfg} ({B.patdnn_variant_name(max(cfg['variant'], 0))})")
+             f"cfg={cfg} ({variant_name(cfg)})")
     torch.cuda.synchronize()
     _log(f"[setup] done in {time.time() - t_setup:.1f} s")
 
@@ -116,7 +121,7 @@ def main() -> int:
     # ------------------------------------------------------------------ roofline of the dominant kernel
     by_kernel = {}
     for k, ly in enumerate(layers):
-        name = B.patdnn_variant_name(max(ly["cfg"]["variant"], 0))
+        name = variant_name(ly["cfg"])
         if ly["spec"].dense or ly["spec"].depthwise:
             continue
         agg = by_kernel.setdefault(name, dict(ms=0.0, flops=0, bytes=0, launches=0))
@@ -148,7 +153,7 @@ def main() -> int:
         t = per_layer_ms[k] * 1e-3
         layer_rows.append({
             "layer": spec.name, "shape": f"{spec.c_in}->{spec.c_out}@{spec.h}", "kept": ly["kept"],
-            "variant": B.patdnn_variant_name(max(ly["cfg"]["variant"], 0)),
+            "variant": variant_name(ly["cfg"]),
             "ck": ly["cfg"]["ck"], "waves": ly["cfg"]["waves"],
             "ms": round(per_layer_ms[k], 4),
             "nz_gflops": round(ly["nz"] / t / 1e9, 1),
@@ -157,6 +162,45 @@ def main() -> int:
             "frac_alu_peak": round(ly["nz"] / t / 1e12 / PEAK_FP32_VECTOR_TFLOPS, 4),
             "frac_hbm_peak": round(ly["bytes"] / t / 8e12, 4),
         })
+
+    # ------------------------------------------------------------------ batch-1 latency of the same stack
+    # (the paper's headline scenario, section 6.2: one image through all CONV layers; reported
+    # beside the throughput number, never instead of it)
+    latency = None
+    if not args.no_latency and args.config == 5:
+        try:
+            one = []
+            for li in range(len(wl.config_layers(2))):
+                d1 = wl.gen_layer(2, li, with_input=False)
+                s1 = d1["spec"]
+                x1 = torch.from_numpy(wl.gen_input_image(s1, 2, li, 0)[None]).cuda()
+                L1 = B.Layer.from_workload(d1)
+                b1 = torch.from_numpy(d1["bias"]).cuda()
+                o1 = torch.empty(L1.output_shape(1, s1.h, s1.w), dtype=torch.float32, device="cuda")
+                if not args.no_tune:
+                    L1.tune(x1, b1, o1)
+                one.append((L1, x1, b1, o1, s1, int(L1.stats()["kept_kernels"])))
+            for _ in range(3):
+                for L1, x1, b1, o1, _, _ in one:
+                    L1.conv2d(x1, b1, o1, relu=True)
+            torch.cuda.synchronize()
+            reps = 20
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                for L1, x1, b1, o1, _, _ in one:
+                    L1.conv2d(x1, b1, o1, relu=True)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms1 = e0.elapsed_time(e1) / reps
+            nz1 = sum(wl.nz_flops(s1, k1) for _, _, _, _, s1, k1 in one)
+            latency = {"workload": wl.CONFIG_NAMES[2], "ms_per_image": round(ms1, 4),
+                       "nz_gflops": round(nz1 / (ms1 * 1e-3) / 1e9, 1),
+                       "note": "13 launches back to back on one stream, launch gaps included"}
+            for L1, *_ in one:
+                L1.close()
+        except Exception as exc:        # the throughput line must not depend on this leg
+            latency = {"error": f"{type(exc).__name__}: {exc}"}
 
     # ------------------------------------------------------------------ dense comparison (same shapes)
     dense_cmp = None
@@ -218,6 +262,7 @@ def main() -> int:
         "nz_gflop_per_step": round(total_nz / 1e9, 2),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "batch1_stack_latency": latency,
         "layers": layer_rows,
         "dense_compare": dense_cmp,
     }

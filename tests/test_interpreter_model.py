@@ -123,11 +123,11 @@ def _model_conv(t, x, bias, pad, relu, stats):
     return out
 
 
-def _check(oracle, d, x, ck, pad=1):
+def _check(oracle, d, x, ck, pad=1, stride=1):
     ref = oracle.conv2d(d["weights"], d["pattern_ids"], d["kernel_mask"], d["pattern_masks"], x,
-                        d["bias"], stride=1, pad=pad, relu=True)
+                        d["bias"], stride=stride, pad=pad, relu=True)
     L = B.Layer(d["weights"], d["pattern_ids"], d["kernel_mask"], d["pattern_masks"], pad=pad,
-                host_only=True)
+                stride=stride, host_only=True)
     seen = []
     for v in range(1, B.patdnn_num_variants()):
         try:
@@ -135,8 +135,10 @@ def _check(oracle, d, x, ck, pad=1):
         except B.PatdnnError as e:
             assert e.status == B.PATDNN_EUNSUPPORTED
             continue
+        assert t["conv_stride"] == stride
         stats = {"instructions": 0, "jumps": 0}
         got = _model_conv(t, x, d["bias"], pad, True, stats)
+        assert got.shape == ref.shape
         assert not np.isnan(got).any(), "an output element was never written"
         err = float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
         kept = int(d["kernel_mask"].sum())
@@ -158,6 +160,8 @@ def test_model_runs_config1_layer(oracle):
     dict(c_out=24, c_in=20, n=2, h=13, w=13, keep=0.3, ck=3, pad=1),     # ragged everywhere
     dict(c_out=10, c_in=5, n=1, h=9, w=20, keep=1.0, ck=16, pad=0),      # every kernel kept: full steps
     dict(c_out=40, c_in=9, n=3, h=8, w=5, keep=0.1, ck=4, pad=1),        # mostly empty chunks
+    dict(c_out=20, c_in=12, n=2, h=15, w=18, keep=0.35, ck=5, pad=1, stride=2),
+    dict(c_out=9, c_in=6, n=1, h=20, w=9, keep=0.5, ck=2, pad=0, stride=2),
 ])
 def test_model_runs_ragged_layers(oracle, case):
     rng = np.random.default_rng(1234 + case["c_out"])
@@ -168,8 +172,9 @@ def test_model_runs_ragged_layers(oracle, case):
          "weights": rng.standard_normal((case["c_out"], case["c_in"], 3, 3)).astype(np.float32),
          "bias": rng.standard_normal(case["c_out"]).astype(np.float32)}
     x = rng.standard_normal((case["n"], case["c_in"], case["h"], case["w"])).astype(np.float32)
-    seen = _check(oracle, d, x, case["ck"], pad=case["pad"])
-    assert len(seen) >= 6
+    stride = case.get("stride", 1)
+    seen = _check(oracle, d, x, case["ck"], pad=case["pad"], stride=stride)
+    assert len(seen) >= (6 if stride == 1 else 2)
 
 
 def test_model_catches_planted_mistakes(oracle):
