@@ -42,6 +42,12 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-compare", action="store_true")
     ap.add_argument("--no-latency", action="store_true", help="skip the batch-1 stack latency leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the library's plain copy kernel once on 256 MiB (for rocprofv3 --pmc "
+                         "runs: its FETCH_SIZE / WRITE_SIZE readings calibrate the counters)")
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "hbm_traffic.json"),
+                    help="per-kernel HBM bytes per launch written by profile_summary.py from --pmc runs "
+                         "of this same command; fills roofline.traffic when it names the dominant kernel")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -98,6 +104,13 @@ def main() -> int:
             if events is not None:
                 events[k][1].record(stream)
 
+    if args.calibrate_copy:
+        src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        B.patdnn_copy_probe(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ------------------------------------------------------------------ timed region
     for _ in range(args.warmup):
         step()
@@ -146,6 +159,22 @@ def main() -> int:
             "hbm_gbps_at_algorithmic_bytes": round(agg["bytes"] / (agg["ms"] * 1e-3) / 1e9, 1),
             "traffic": None,
         }
+        # HBM bytes per launch from hardware counters, if a counter run of this command was summarised
+        try:
+            vi = next(ly["cfg"]["variant"] for ly in layers if variant_name(ly["cfg"]) == kname)
+            info = B.patdnn_tiled_info(next(ly["L"].handle for ly in layers if variant_name(ly["cfg"]) == kname), vi)
+            sig = (f"Geo<{info['G']}, {info['patch_rows']}, {info['patch_cols']}, {info['conv_stride']}, "
+                   f"{info['lanes_x']}, false,")
+            with open(args.traffic_json) as f:
+                table = json.load(f)
+            hit = [v for k, v in table.items() if sig in k and "fetch_bytes" in v and "write_bytes" in v]
+            if hit:
+                roofline["traffic"] = round(hit[0]["fetch_bytes"] + hit[0]["write_bytes"])
+                roofline["traffic_detail"] = {"fetch_bytes_per_launch": round(hit[0]["fetch_bytes"]),
+                                              "write_bytes_per_launch": round(hit[0]["write_bytes"]),
+                                              "source": os.path.relpath(args.traffic_json, ROOT)}
+        except (OSError, ValueError, StopIteration, KeyError, B.PatdnnError):
+            pass
 
     layer_rows = []
     for k, ly in enumerate(layers):

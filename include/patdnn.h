@@ -230,6 +230,15 @@ patdnn_status_t patdnn_export_tiled(patdnn_handle_t h, int32_t variant, int32_t 
                                     uint32_t* chunk_ptr,     /* [num_groups*num_chunks] */
                                     uint32_t* steps);        /* [num_steps*24] */
 
+/*
+ * Measurement aid, not part of the method: copies `bytes` (a multiple of 16; both
+ * pointers DEVICE, 16-byte aligned, not overlapping) with a plain kernel,
+ * asynchronously on `stream`.  Profiled beside the convolution kernels it calibrates
+ * hardware traffic counters: it reads and writes exactly `bytes`.  PATDNN_EINVAL on
+ * a null / misaligned pointer or size, PATDNN_EHIP if the launch fails.
+ */
+patdnn_status_t patdnn_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
+
 void        patdnn_destroy(patdnn_handle_t h);          /* NULL is a no-op */
 const char* patdnn_status_string(patdnn_status_t s);
 const char* patdnn_last_error(void);

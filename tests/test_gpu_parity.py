@@ -234,3 +234,16 @@ def test_full_size_sampled(torch, oracle, layer):
                              x[n:n + 1], d["bias"], relu=True, dense=spec.dense, skip_removed=True)
         assert _rel_err(got[n:n + 1], full) <= TOL
     L.close()
+
+
+def test_copy_probe_copies_exactly(torch):
+    """The plain copy kernel used to calibrate traffic counters moves every byte."""
+    src = torch.arange(0, (1 << 20) + 12, dtype=torch.int32, device="cuda")
+    buf = torch.full((src.numel() + 8,), -7, dtype=torch.int32, device="cuda")
+    dst = buf[4:4 + src.numel()]
+    B.patdnn_copy_probe(dst, src)
+    torch.cuda.synchronize()
+    assert bool((dst == src).all())
+    assert bool((buf[:4] == -7).all()) and bool((buf[-4:] == -7).all())
+    with pytest.raises(B.PatdnnError):
+        B.patdnn_copy_probe(dst[1:5], src[1:5])          # misaligned
