@@ -132,7 +132,8 @@ def main(argv=None) -> int:
             print(f"    {key} (scaled) | {val:.6g}")
     if args.json:
         with open(args.json, "w") as f:
-            json.dump({k: v for k, v in traffic.items() if only.search(k)}, f, indent=1, sort_keys=True)
+            json.dump({k: v for k, v in traffic.items() if only.search(k) and not (copy and copy.search(k))},
+                      f, indent=1, sort_keys=True)
     return 0
 
 
