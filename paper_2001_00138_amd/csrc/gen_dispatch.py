@@ -295,15 +295,16 @@ def _program_threaded(G, PR, PC, S, TGX, MODE, g):
         for slot in range(G):
             for taps in universe():
                 asm.begin_block(block_log2)
-                for line in _fmas(G, PR, PC, S, g, ws, slot, taps):
-                    asm(line)
-                # next record -> weight registers, its block -> PC
-                asm(f"s_movrels_b64 s[{W}:{W + 1}], s[{SET_A}:{SET_A + 1}]")
-                asm(f"s_movrels_b64 s[{W + 2}:{W + 3}], s[{SET_A + 2}:{SET_A + 3}]")
+                # the next record's block address first: it is ready long before the jump
                 asm(f"s_movrels_b32 s{TGT}, s{SET_A + 4}")
-                asm(f"s_add_u32 m0, m0, {T_REC_DWORDS}")
                 asm(f"s_add_u32 s{TGT}, s{TGT}, s{BASE}")
                 asm(f"s_addc_u32 s{TGT + 1}, s{BASE + 1}, 0")
+                for line in _fmas(G, PR, PC, S, g, ws, slot, taps):
+                    asm(line)
+                # next record -> weight registers (the FMAs above have read the current ones)
+                asm(f"s_movrels_b64 s[{W}:{W + 1}], s[{SET_A}:{SET_A + 1}]")
+                asm(f"s_movrels_b64 s[{W + 2}:{W + 3}], s[{SET_A + 2}:{SET_A + 3}]")
+                asm(f"s_add_u32 m0, m0, {T_REC_DWORDS}")
                 asm(f"s_setpc_b64 s[{TGT}:{TGT + 1}]")
                 asm.end_block(block_log2)
     asm(".Lexit%=:")
