@@ -221,6 +221,8 @@ typedef struct {
     int32_t conv_stride;
     int32_t lanes_x;               /* lanes across a band; a wavefront covers 64/lanes_x bands */
     int32_t experimental;          /* needs PATDNN_EXPERIMENTAL=1 to run */
+    int32_t mode;                  /* interpreter build: bit 0 double_window, bit 1 threaded,
+                                      bit 2 window in fixed registers read two floats at a time */
 } patdnn_tiled_info_t;
 
 patdnn_status_t patdnn_tiled_info(patdnn_handle_t h, int32_t variant, int32_t ck,

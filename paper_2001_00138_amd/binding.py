@@ -60,7 +60,8 @@ class TiledInfo(ctypes.Structure):
                 ("double_window", ctypes.c_int32), ("lds_channel_bytes", ctypes.c_int32),
                 ("threaded", ctypes.c_int32), ("patch_rows", ctypes.c_int32),
                 ("patch_cols", ctypes.c_int32), ("conv_stride", ctypes.c_int32),
-                ("lanes_x", ctypes.c_int32), ("experimental", ctypes.c_int32)]
+                ("lanes_x", ctypes.c_int32), ("experimental", ctypes.c_int32),
+                ("mode", ctypes.c_int32)]
 
 
 class PatdnnError(RuntimeError):

@@ -11,7 +11,8 @@ specialisation
     };
 
 whose body is ONE inline-assembly statement, hand-scheduled for gfx950.
-MODE bit 0: two sets of window registers; bit 1: threaded dispatch.
+MODE bit 0: two sets of window registers; bit 1: threaded dispatch; bit 2: the window
+lives in fixed vector registers and is read from LDS two floats at a time.
 
 The encoder turns the kept kernels of one filter group and one chunk of staged input
 channels into a sequence of fixed-size *steps* (24 dwords each); all kernels of a step
@@ -105,6 +106,7 @@ def geometry(G, PR, PC, S, TGX, MODE):
     num_ctrl = T_NUM_CTRL if threaded else C_NUM_CTRL
     return dict(WR=WR, WC=WC, pitch=pitch, nacc=nacc, nwin=WR * WC, block_bytes=block_bytes,
                 table_off=num_ctrl * CTRL_SLOT, sets=2 if MODE & 1 else 1, threaded=threaded,
+                wide=bool(MODE & 4),
                 records=T_RECORDS if threaded else C_RECORDS, ctrl_bytes=CTRL_SLOT,
                 clobber=T_CLOBBER if threaded else C_CLOBBER)
 
@@ -129,7 +131,24 @@ class _Asm:
         self.nblocks += 1
 
 
+WIDE_WINDOW_BASE = 128         # first fixed window register of MODE bit 2
+
+
+def _win(g, ws, i):
+    """Operand text of window register i of set ws."""
+    if g["wide"]:
+        return f"v{WIDE_WINDOW_BASE + ws * g['nwin'] + i}"
+    return f"%[x{ws}_{i}]"
+
+
 def _window_reads(asm, g, ws):
+    if g["wide"]:
+        # rows start 8-byte aligned in LDS (even patch width, even pitch): two floats per read
+        for q in range(g["WR"]):
+            for r in range(0, g["WC"], 2):
+                v = WIDE_WINDOW_BASE + ws * g["nwin"] + q * g["WC"] + r
+                asm(f"ds_read_b64 v[{v}:{v + 1}], %[addr] offset:{4 * (q * g['pitch'] + r)}")
+        return
     for i in range(g["nwin"]):
         q, r = divmod(i, g["WC"])
         asm(f"ds_read_b32 %[x{ws}_{i}], %[addr] offset:{4 * (q * g['pitch'] + r)}")
@@ -142,7 +161,7 @@ def _fmas(G, PR, PC, S, g, ws, slot, taps):
         for r in range(PR):
             for c in range(PC):
                 x = (r * S + kh) * g["WC"] + c * S + kw
-                out.append(f"v_fmac_f32 %[a{slot}_{r * PC + c}], s{W + t}, %[x{ws}_{x}]")
+                out.append(f"v_fmac_f32 %[a{slot}_{r * PC + c}], s{W + t}, {_win(g, ws, x)}")
     return out
 
 
@@ -317,6 +336,8 @@ def program(G, PR, PC, S, TGX, MODE):
     staged chunk, %[sp] the 64-bit address of the first step, %[entry] (threaded) the
     code offset of the first step transition."""
     g = geometry(G, PR, PC, S, TGX, MODE)
+    if g["wide"] and (g["WC"] % 2 or (PC * S) % 2 or g["nwin"] % 2):
+        raise ValueError("wide window reads need an even window width and an even lane step")
     build = _program_threaded if g["threaded"] else _program_call
     return build(G, PR, PC, S, TGX, MODE, g), g
 
@@ -337,7 +358,8 @@ def generate(G, PR, PC, S, TGX, MODE):
     emit(f"    static __device__ __forceinline__ void run(float (&acc)[{G}][{nacc}], unsigned lane_lds,")
     emit("                                               const uint32_t* stream, unsigned entry)")
     emit("    {")
-    emit(f"        float win[{sets}][{nwin}];")
+    if not g["wide"]:
+        emit(f"        float win[{sets}][{nwin}];")
     emit("        unsigned addr;")
     if not g["threaded"]:
         emit("        (void)entry;")
@@ -352,13 +374,16 @@ def generate(G, PR, PC, S, TGX, MODE):
     if chunk:
         emit('            "' + "\\n".join(chunk) + '\\n"')
     outs = ", ".join(f'[a{s}_{i}] "+v"(acc[{s}][{i}])' for s in range(G) for i in range(nacc))
-    outs += ", " + ", ".join(f'[x{ws}_{i}] "=&v"(win[{ws}][{i}])' for ws in range(sets) for i in range(nwin))
+    if not g["wide"]:
+        outs += ", " + ", ".join(f'[x{ws}_{i}] "=&v"(win[{ws}][{i}])' for ws in range(sets) for i in range(nwin))
     outs += ', [addr] "=&v"(addr)'
     ins = '[lane] "v"(lane_lds), [sp] "s"(stream)'
     if g["threaded"]:
         ins += ', [entry] "s"(entry)'
     lo, hi = g["clobber"]
     clob = ", ".join(f'"s{i}"' for i in range(lo, hi + 1))
+    if g["wide"]:
+        clob += ", " + ", ".join(f'"v{WIDE_WINDOW_BASE + i}"' for i in range(sets * nwin))
     emit(f"            : {outs}")
     emit(f"            : {ins}")
     emit(f'            : {clob}, "scc", "memory");')

@@ -296,7 +296,7 @@ PATDNN_VARIANTS
 
 static const TiledVariant kVariants[] = {
 #define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, MODE, EXPERIMENTAL)                    \
-    {#name, G, PR, PC, S, TGX, DENSE, ((MODE) & 1) != 0, ((MODE) & 2) != 0, EXPERIMENTAL != 0, \
+    {#name, G, PR, PC, S, TGX, DENSE, ((MODE) & 1) != 0, ((MODE) & 2) != 0, EXPERIMENTAL != 0, MODE, \
      Geo_##name::TILEP, Geo_##name::TILEP,                                                 \
      MAXSLOTS, Stream_##name::kBlockBytes, Stream_##name::kTableOff, Stream_##name::kCtrlBytes, \
      Stream_##name::kRecords, &launch_tiled<Geo_##name>},

@@ -569,6 +569,7 @@ patdnn_status_t patdnn_tiled_info(patdnn_handle_t h, int32_t variant, int32_t ck
     out->conv_stride = v.S;
     out->lanes_x = v.TGX;
     out->experimental = v.experimental ? 1 : 0;
+    out->mode = v.mode;
     return PATDNN_OK;
 }
 

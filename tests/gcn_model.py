@@ -157,8 +157,13 @@ class Wave:
         self.s[lo] = v & 0xFFFFFFFF
         self.s[hi] = (v >> 32) & 0xFFFFFFFF
 
+    @staticmethod
+    def vkey(a: str) -> str:
+        """Vector operand -> key: the name of a %[...] operand, or a fixed register vN."""
+        return a[2:-1] if a.startswith("%[") else a
+
     def vreg(self, a: str) -> np.ndarray:
-        name = a[2:-1]
+        name = self.vkey(a)
         if name in self.pending_v:
             raise ModelError(f"vector operand {name} used while an LDS read into it is in flight")
         if name not in self.v:
@@ -194,19 +199,30 @@ class Wave:
                 wv = np.array([self.rd32(a[1])], dtype=np.uint32).view(np.float32)[0]
                 x = self.vreg(a[2]).view(np.float32)
                 r = (np.float64(wv) * x.astype(np.float64) + d.view(np.float32).astype(np.float64))
-                self.v[a[0][2:-1]] = r.astype(np.float32).view(np.uint32)
+                self.v[self.vkey(a[0])] = r.astype(np.float32).view(np.uint32)
             elif op == "ds_read_b32":
                 va = self.vreg(a[1]).astype(np.int64) + off
                 if (va % 4).any() or (va < 0).any() or (va + 4 > self.lds.size * 4).any():
                     raise ModelError(f"LDS read out of the staged region at {addr - CODE_BASE:#x}")
-                if a[0][2:-1] in self.pending_v:
+                if self.vkey(a[0]) in self.pending_v:
                     raise ModelError("two LDS reads in flight into one register")
-                self.pending_v[a[0][2:-1]] = self.lds[va // 4].copy()
+                self.pending_v[self.vkey(a[0])] = self.lds[va // 4].copy()
+            elif op == "ds_read_b64":
+                va = self.vreg(a[1]).astype(np.int64) + off
+                if (va % 8).any() or (va < 0).any() or (va + 8 > self.lds.size * 4).any():
+                    raise ModelError(f"misaligned or out-of-range 64-bit LDS read at {addr - CODE_BASE:#x}")
+                lo, hi = re.match(r"^v\[(\d+):(\d+)\]$", a[0]).groups()
+                if int(hi) != int(lo) + 1 or int(lo) % 2:
+                    raise ModelError(f"bad 64-bit destination {a[0]}")
+                for k in range(2):
+                    if f"v{int(lo) + k}" in self.pending_v:
+                        raise ModelError("two LDS reads in flight into one register")
+                    self.pending_v[f"v{int(lo) + k}"] = self.lds[va // 4 + k].copy()
             elif op == "v_add_u32":
                 src0 = a[1]
-                x0 = self.vreg(src0) if src0.startswith("%[") and src0[2:-1] in self.v else \
+                x0 = self.vreg(src0) if self.vkey(src0) in self.v else \
                     np.full(WAVE, self.rd32(src0), dtype=np.uint32)
-                self.v[a[0][2:-1]] = (x0.astype(np.uint64) + self.vreg(a[2])).astype(np.uint32)
+                self.v[self.vkey(a[0])] = (x0.astype(np.uint64) + self.vreg(a[2])).astype(np.uint32)
             elif op in ("s_add_u32", "s_addc_u32"):
                 r = self.rd32(a[1]) + self.rd32(a[2]) + (self.scc if op == "s_addc_u32" else 0)
                 self.scc = 1 if r >> 32 else 0

@@ -32,7 +32,7 @@ def _built():
 
 def _program(t):
     key = (t["G"], t["patch_rows"], t["patch_cols"], t["conv_stride"], t["lanes_x"],
-           t["double_window"] | (t["threaded"] << 1))
+           t["mode"])
     if key not in _programs:
         lines, geo = gen_dispatch.program(*key)
         assert geo["block_bytes"] == t["block_bytes"] and geo["table_off"] == t["table_off"]
@@ -153,7 +153,7 @@ def _check(oracle, d, x, ck, pad=1, stride=1):
 def test_model_runs_config1_layer(oracle):
     d = wl.gen_layer(1, 0)
     seen = _check(oracle, d, d["input"], 8)
-    assert len(seen) >= 6
+    assert len(seen) >= 7
 
 
 @pytest.mark.parametrize("case", [
@@ -174,7 +174,7 @@ def test_model_runs_ragged_layers(oracle, case):
     x = rng.standard_normal((case["n"], case["c_in"], case["h"], case["w"])).astype(np.float32)
     stride = case.get("stride", 1)
     seen = _check(oracle, d, x, case["ck"], pad=case["pad"], stride=stride)
-    assert len(seen) >= (6 if stride == 1 else 2)
+    assert len(seen) >= (7 if stride == 1 else 2)
 
 
 def test_model_catches_planted_mistakes(oracle):
@@ -184,7 +184,8 @@ def test_model_catches_planted_mistakes(oracle):
     L = B.Layer.from_workload(d, host_only=True)
     t = L.export_tiled(1, 8)                       # call dispatch, one window set
     L.close()
-    key = (t["G"], t["patch_rows"], t["patch_cols"], t["conv_stride"], t["lanes_x"], 0)
+    key = (t["G"], t["patch_rows"], t["patch_cols"], t["conv_stride"], t["lanes_x"], t["mode"])
+    assert t["mode"] == 0
     lines, _ = gen_dispatch.program(*key)
     stats = {"instructions": 0, "jumps": 0}
     # 1. the wait that ends the window load is removed
