@@ -1,0 +1,155 @@
+"""csrc/kernel_tiled.hip compiled as plain C++ for the host (tests/host_model/): one OS
+thread per GPU thread, LDS as a poisoned array, buffer loads with the descriptor's range
+check, every LDS / tensor access bounds-checked, the assembly interpreter replaced by a
+C++ walk of the same streams.  Every tiled variant - also the ones not yet run on
+hardware - computes small ragged layers here and is compared with the oracle, so that
+an indexing mistake in a new tile geometry is found on the CPU."""
+
+import ctypes
+import os
+import shutil
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+from conftest import ROOT
+from paper_2001_00138_amd import binding as B
+from paper_2001_00138_amd import workloads as wl
+
+CSRC = os.path.join(ROOT, "paper_2001_00138_amd", "csrc")
+sys.path.insert(0, CSRC)
+import gen_dispatch  # noqa: E402
+
+TOL = 1e-5
+
+
+def _model_inc(geos):
+    out = []
+    for (G, PR, PC, S, TGX, MODE) in geos:
+        g = gen_dispatch.geometry(G, PR, PC, S, TGX, MODE)
+        out.append(f"""template <> struct StreamLoop<{G}, {PR}, {PC}, {S}, {TGX}, {MODE}> {{
+    static constexpr unsigned kBlockBytes = {g['block_bytes']}u, kTableOff = {g['table_off']}u,
+                              kCtrlBytes = {g['ctrl_bytes']}u, kRecords = {g['records']}u;
+    static void run(float (&acc)[{G}][{g['nacc']}], unsigned lane_lds, const uint32_t* stream, unsigned entry)
+    {{
+        static const HostmodelGeo g{{{G}, {PR}, {PC}, {S}, {g['WR']}, {g['WC']}, {g['pitch']},
+                                    {g['block_bytes']}u, {g['table_off']}u, {g['ctrl_bytes']}u, {g['records']}u,
+                                    {g['sets']}, {int(g['threaded'])}}};
+        hostmodel_walk(g, &acc[0][0], lane_lds, stream, entry);
+    }}
+}};
+""")
+    return "".join(out)
+
+
+def _build_hostmodel(build, edit=None):
+    """Compiles the host model in `build`; `edit(text) -> text` may plant a mistake in the
+    copy of kernel_tiled.hip."""
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2001_00138_amd import buildlib
+        buildlib.build()
+    from paper_2001_00138_amd import buildlib
+    csrc = build / "pkg" / "csrc"
+    (csrc / "gen").mkdir(parents=True)
+    (build / "include").mkdir()
+    for f in ("kernel_tiled.hip", "kernels.hpp", "layout.hpp", "variants.def"):
+        shutil.copy(os.path.join(CSRC, f), csrc / f)
+    if edit:
+        text = (csrc / "kernel_tiled.hip").read_text()
+        changed = edit(text)
+        assert changed != text, "the planted edit did not apply"
+        (csrc / "kernel_tiled.hip").write_text(changed)
+    shutil.copy(os.path.join(ROOT, "include", "patdnn.h"), build / "include" / "patdnn.h")
+    (csrc / "gen" / "dispatch_all.inc").write_text(_model_inc(buildlib.sparse_geometries()))
+    lib = build / "libhostmodel.so"
+    cmd = ["g++", "-O1", "-std=c++17", "-pthread", "-fPIC", "-shared", "-Wno-unknown-pragmas", "-Wno-attributes",
+           "-I", os.path.join(ROOT, "tests", "host_model"), "-I", str(csrc),
+           os.path.join(ROOT, "tests", "host_model", "hostmodel.cpp"), "-o", str(lib)]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-4000:]
+    L = ctypes.CDLL(str(lib))
+    L.hostmodel_run.restype = ctypes.c_long
+    L.hostmodel_run.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p] * 4 + [ctypes.c_int] * 10 + \
+                               [ctypes.c_void_p] * 3 + [ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
+    return L
+
+
+@pytest.fixture(scope="module")
+def hostmodel(tmp_path_factory):
+    return _build_hostmodel(tmp_path_factory.mktemp("hostmodel"))
+
+
+def _run(hostmodel, v, t, x, bias, pad, stride, relu, waves, c_out, w9=None):
+    n, c_in, h, w = x.shape
+    ho, wo = (h + 2 * pad - 3) // stride + 1, (w + 2 * pad - 3) // stride + 1
+    guard = 1024
+    buf = np.full(n * c_out * ho * wo + 2 * guard, 777.0, np.float32)
+    out = buf[guard:-guard]
+    out[:] = np.nan
+    msg = ctypes.create_string_buffer(512)
+    x = np.ascontiguousarray(x)
+    ptr = lambda a: None if a is None else a.ctypes.data
+    errs = hostmodel.hostmodel_run(v - 1, t["G"], t["num_groups"], t["ck"], t["num_chunks"],
+                                   ptr(t["slot_channel"]), ptr(t.get("chunk_ptr")), ptr(t.get("steps")), ptr(w9),
+                                   n, c_in, c_out, h, w, ho, wo, stride, pad, int(relu), ptr(x), ptr(bias),
+                                   out.ctypes.data, waves, msg, 512)
+    assert errs == 0, msg.value.decode()
+    assert (buf[:guard] == 777.0).all() and (buf[-guard:] == 777.0).all(), "write outside the output tensor"
+    return out.reshape(n, c_out, ho, wo)
+
+
+CASES = [
+    dict(c_out=24, c_in=20, n=2, h=13, w=13, keep=0.3, ck=3, waves=2, pad=1),
+    dict(c_out=40, c_in=9, n=3, h=8, w=21, keep=0.25, ck=16, waves=4, pad=1),
+    dict(c_out=16, c_in=6, n=1, h=30, w=37, keep=0.6, ck=4, waves=3, pad=0),
+    dict(c_out=20, c_in=12, n=2, h=15, w=18, keep=0.35, ck=5, waves=2, pad=1, stride=2),
+    dict(c_out=9, c_in=6, n=1, h=20, w=9, keep=0.5, ck=2, waves=4, pad=0, stride=2),
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_every_sparse_variant_on_the_host_model(hostmodel, oracle, case):
+    rng = np.random.default_rng(4321 + case["c_out"] + case["h"])
+    lib = wl.pattern_library(wl.PATTERN_SEED)
+    stride = case.get("stride", 1)
+    ids = rng.integers(0, 8, (case["c_out"], case["c_in"]), dtype=np.uint8)
+    mask = (rng.random((case["c_out"], case["c_in"])) < case["keep"]).astype(np.uint8)
+    w = rng.standard_normal((case["c_out"], case["c_in"], 3, 3)).astype(np.float32)
+    bias = rng.standard_normal(case["c_out"]).astype(np.float32)
+    x = rng.standard_normal((case["n"], case["c_in"], case["h"], case["w"])).astype(np.float32)
+    ref = oracle.conv2d(w, ids, mask, lib, x, bias, stride=stride, pad=case["pad"], relu=True)
+    L = B.Layer(w, ids, mask, lib, stride=stride, pad=case["pad"], host_only=True)
+    seen = 0
+    for v in range(1, B.patdnn_num_variants()):
+        try:
+            t = L.export_tiled(v, case["ck"])
+        except B.PatdnnError as e:
+            assert e.status == B.PATDNN_EUNSUPPORTED
+            continue
+        lds_per_channel = hostmodel.hostmodel_variant_lds_floats(v - 1)
+        min_waves = -(-lds_per_channel // (64 * 16))        # enough staging slots for any compiled variant
+        got = _run(hostmodel, v, t, x, bias, case["pad"], stride, True, max(case["waves"], min_waves, 3),
+                   case["c_out"])
+        assert not np.isnan(got).any(), (B.patdnn_variant_name(v), "output element never written or unstaged LDS read")
+        err = float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
+        print(f"  {B.patdnn_variant_name(v)}: rel_err={err:.2e}")
+        assert err <= TOL, (B.patdnn_variant_name(v), err)
+        seen += 1
+    L.close()
+    assert seen >= 2
+
+
+@pytest.mark.parametrize("plant", ["staging column", "epilogue guard", "lane offset"])
+def test_host_model_catches_planted_mistakes(tmp_path, oracle, plant):
+    edits = {
+        "staging column": lambda t: t.replace("const int ix = bxi * TGX * PC * S - a.pad + x;",
+                                              "const int ix = bxi * TGX * PC * S - a.pad + x + 1;"),
+        "epilogue guard": lambda t: t.replace("if (oy < a.ho && ox < a.wo) dst", "if (ox < a.wo) dst"),
+        "lane offset": lambda t: t.replace("const int lane_off = lb * PITCH + gx * PC * S;",
+                                           "const int lane_off = lb * PITCH + gx * PC * S + GEO::ROWP * 3;"),
+    }
+    broken = _build_hostmodel(tmp_path, edits[plant])
+    with pytest.raises(AssertionError):
+        test_every_sparse_variant_on_the_host_model(broken, oracle, CASES[0])
