@@ -147,13 +147,17 @@ patdnn_status_t patdnn_layout_stats(patdnn_handle_t h, patdnn_stats_t* out);
  *                           (section 5.4 load-redundancy elimination); see
  *                           patdnn_variant_name
  * `ck` = input channels staged per LDS pass, `waves` = wavefronts (filter groups)
- * per workgroup; 0 lets the library choose.
+ * per workgroup; 0 lets the library choose.  `ksplit` > 1 (tiled sparse variants;
+ * experimental, needs PATDNN_EXPERIMENTAL=1) cuts the input channels into that many
+ * slices handled by different workgroups, whose partial sums are added into the output
+ * with atomic adds between a zero-fill and a bias + ReLU kernel (three launches; the
+ * summation order then varies from run to run within fp32 rounding); 0 or 1 = off.
  */
 typedef struct {
     int32_t variant;
     int32_t ck;
     int32_t waves;
-    int32_t reserved;
+    int32_t ksplit;
 } patdnn_config_t;
 
 #define PATDNN_VARIANT_FKW 0

@@ -49,7 +49,7 @@ class Stats(ctypes.Structure):
 
 class Config(ctypes.Structure):
     _fields_ = [("variant", ctypes.c_int32), ("ck", ctypes.c_int32), ("waves", ctypes.c_int32),
-                ("reserved", ctypes.c_int32)]
+                ("ksplit", ctypes.c_int32)]
 
 
 class TiledInfo(ctypes.Structure):
@@ -226,15 +226,15 @@ def patdnn_variant_name(v: int) -> Optional[str]:
     return None if s is None else s.decode()
 
 
-def patdnn_set_config(handle: int, variant: int, ck: int = 0, waves: int = 0) -> None:
-    c = Config(variant, ck, waves, 0)
+def patdnn_set_config(handle: int, variant: int, ck: int = 0, waves: int = 0, ksplit: int = 0) -> None:
+    c = Config(variant, ck, waves, ksplit)
     _check(lib().patdnn_set_config(handle, ctypes.byref(c)))
 
 
 def patdnn_get_config(handle: int) -> dict:
     c = Config()
     _check(lib().patdnn_get_config(handle, ctypes.byref(c)))
-    return {"variant": c.variant, "ck": c.ck, "waves": c.waves}
+    return {"variant": c.variant, "ck": c.ck, "waves": c.waves, "ksplit": c.ksplit}
 
 
 def patdnn_tune(handle: int, x, bias, out, *, stream=None) -> float:
@@ -314,8 +314,8 @@ class Layer:
     def stats(self):
         return patdnn_layout_stats(self.handle)
 
-    def set_config(self, variant, ck=0, waves=0):
-        patdnn_set_config(self.handle, variant, ck, waves)
+    def set_config(self, variant, ck=0, waves=0, ksplit=0):
+        patdnn_set_config(self.handle, variant, ck, waves, ksplit)
 
     def get_config(self):
         return patdnn_get_config(self.handle)

@@ -26,6 +26,7 @@
 //     index ranges over the 56 centre-keeping patterns of section 4.1.
 //   * Dense (unpruned) layers use the same staging and register tiling with a plain
 //     9-tap loop and no stream.
+#include <algorithm>
 #include <type_traits>
 
 #include "kernels.hpp"
@@ -87,7 +88,11 @@ __device__ __forceinline__ T load_uniform(const T* p, size_t i)
 
 typedef __attribute__((address_space(3))) float lds_f32;
 
-template <class GEO>
+// SPLITK: the workgroup covers only the chunks [chunk_first, chunk_last) of the input
+// channels and ADDS its partial sums to the output (which the launcher zeroed; bias and
+// ReLU are applied by a finishing kernel): more workgroups for layers with few tiles.
+// blockIdx.y = slice of the input channels: chunks [y*n/k, (y+1)*n/k), k = gridDim.y.
+template <class GEO, bool SPLITK>
 __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
 {
     constexpr int G = GEO::G, PR = GEO::PR, PC = GEO::PC, S = GEO::S, TGX = GEO::TGX;
@@ -162,7 +167,9 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     // ---- this lane's patch
     const int lb = lane / TGX, gx = lane - lb * TGX;
     const int my_band = band0 + lb;
-    const bool band_ok = my_band < a.num_bands;
+    // when TGX does not divide 64 the last lanes of the wavefront have no band
+    const bool lane_ok = (64 % TGX == 0) || lb < NB;
+    const bool band_ok = lane_ok && my_band < a.num_bands;
     int img = 0, oy0 = 0, ox0 = 0;
     if (band_ok) {
         const int bxi = my_band % a.bx, t = my_band / a.bx;
@@ -171,7 +178,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
         oy0 = byi * PR;
         ox0 = (bxi * TGX + gx) * PC;
     }
-    const int lane_off = lb * PITCH + gx * PC * S;           // floats, inside one staged channel
+    const int lane_off = lane_ok ? lb * PITCH + gx * PC * S : 0;   // floats, inside one staged channel
 
     float acc[G][GEO::NACC];
 #pragma unroll
@@ -181,15 +188,22 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
 
     const bool group_ok = group < a.num_groups;
 
-    stage(0, lds3);
-    for (int c0 = 0, chunk = 0; c0 < a.c_in; c0 += a.ck, ++chunk) {
+    int chunk_first = 0, c_first = 0, c_end = a.c_in;
+    if constexpr (SPLITK) {
+        const int k = (int)gridDim.y, y = (int)blockIdx.y;
+        chunk_first = (int)((long long)a.num_chunks * y / k);
+        c_first = chunk_first * a.ck;
+        c_end = min(a.c_in, (int)((long long)a.num_chunks * (y + 1) / k) * a.ck);
+    }
+    stage(c_first, lds3);
+    for (int c0 = c_first, chunk = SPLITK ? chunk_first : 0; c0 < c_end; c0 += a.ck, ++chunk) {
         const int cn = min(a.ck, a.c_in - c0);
-        const int cur = (chunk & 1) * buf_floats;
+        const int cur = ((SPLITK ? chunk - chunk_first : chunk) & 1) * buf_floats;
         // chunk `chunk` has landed in this wavefront's view, and (barrier) in everyone's;
         // everyone has also finished reading the other buffer
         __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
         __syncthreads();
-        if (c0 + a.ck < a.c_in) stage(c0 + a.ck, lds3 + (buf_floats - cur));
+        if (c0 + a.ck < c_end) stage(c0 + a.ck, lds3 + (buf_floats - cur));
 
         if (group_ok) {
             if constexpr (GEO::DENSE) {
@@ -243,17 +257,41 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
 #pragma unroll
                 for (int c = 0; c < PC; ++c) {
                     const int oy = oy0 + r, ox = ox0 + c;
-                    float v = acc[s][r * PC + c] + b;
-                    if (a.relu) v = fmaxf(v, 0.0f);
-                    if (oy < a.ho && ox < a.wo) dst[(size_t)oy * a.wo + ox] = v;
+                    if constexpr (SPLITK) {
+                        if (oy < a.ho && ox < a.wo) unsafeAtomicAdd(&dst[(size_t)oy * a.wo + ox], acc[s][r * PC + c]);
+                    } else {
+                        float v = acc[s][r * PC + c] + b;
+                        if (a.relu) v = fmaxf(v, 0.0f);
+                        if (oy < a.ho && ox < a.wo) dst[(size_t)oy * a.wo + ox] = v;
+                    }
                 }
         }
     }
 }
 
+__global__ __launch_bounds__(256) void fill_zero_kernel(float* p, size_t n)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.0f;
+}
+
+// out[n][c][pixel] = act(out + bias[c]) in place, after the split kernels have added up
+__global__ __launch_bounds__(256) void bias_act_kernel(float* out, const float* bias, int c_out, size_t plane,
+                                                       size_t total, int relu)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        float v = out[i];
+        if (bias) v += bias[(i / plane) % (size_t)c_out];
+        if (relu) v = fmaxf(v, 0.0f);
+        out[i] = v;
+    }
+}
+
 template <class GEO>
 static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const float* in,
-                               const float* bias, float* out, int32_t waves, hipStream_t stream)
+                               const float* bias, float* out, int32_t waves, int32_t ksplit,
+                               hipStream_t stream)
 {
     TiledArgs a{};
     a.in = in; a.bias = bias; a.out = out;
@@ -274,14 +312,37 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
     const size_t lds_bytes = 2 * (size_t)t.ck * GEO::TILEP * sizeof(float);     // two staging buffers
     static bool big_lds_allowed = false;
     if (lds_bytes > 64 * 1024 && !big_lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         big_lds_allowed = true;
     }
-    hipLaunchKernelGGL(tiled_conv_kernel<GEO>, dim3((unsigned)blocks), dim3(64 * waves), lds_bytes,
-                       stream, a);
-    return hipGetLastError();
+    if (ksplit <= 1) {
+        hipLaunchKernelGGL((tiled_conv_kernel<GEO, false>), dim3((unsigned)blocks), dim3(64 * waves), lds_bytes,
+                           stream, a);
+        return hipGetLastError();
+    }
+    // split over the input channels: zero the output, add the slices up, then bias + ReLU
+    if constexpr (GEO::DENSE) {
+        return hipErrorInvalidValue;
+    } else {
+        if (ksplit > t.num_chunks || ksplit > 65535) return hipErrorInvalidValue;
+        static bool big_lds_allowed_k = false;
+        if (lds_bytes > 64 * 1024 && !big_lds_allowed_k) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            if (e != hipSuccess) return e;
+            big_lds_allowed_k = true;
+        }
+        const size_t plane = (size_t)s.ho * s.wo, total = (size_t)s.n * s.c_out * plane;
+        const unsigned fill_blocks = (unsigned)std::min<size_t>((total + 255) / 256, 256 * 32);
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(fill_blocks), dim3(256), 0, stream, out, total);
+        hipLaunchKernelGGL((tiled_conv_kernel<GEO, true>), dim3((unsigned)blocks, (unsigned)ksplit), dim3(64 * waves),
+                           lds_bytes, stream, a);
+        hipLaunchKernelGGL(bias_act_kernel, dim3(fill_blocks), dim3(256), 0, stream, out, bias, s.c_out, plane,
+                           total, s.relu);
+        return hipGetLastError();
+    }
 }
 
 // X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, MODE, EXPERIMENTAL) - one line per compiled variant

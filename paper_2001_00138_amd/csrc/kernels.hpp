@@ -63,8 +63,9 @@ struct TiledVariant {
     uint32_t table_off;               // offset of block 0 from the code base
     uint32_t ctrl_bytes;              // control block k sits at k*ctrl_bytes
     uint32_t records;                 // kernels per step
+    // ksplit > 1 (sparse variants): slices of the input channels on gridDim.y, summed with atomics
     hipError_t (*launch)(const DevTiled&, const ConvShape&, const float*, const float*, float*,
-                         int32_t waves, hipStream_t);
+                         int32_t waves, int32_t ksplit, hipStream_t);
 };
 
 int num_tiled_variants();

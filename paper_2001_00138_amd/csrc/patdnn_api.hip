@@ -49,7 +49,7 @@ struct patdnn_layer {
     // by (variant index, ck); dense variants use ck = 0
     std::map<std::pair<int, int>, std::unique_ptr<TiledOnDevice>> tiled;
     std::vector<void*> allocations;
-    patdnn_config_t cfg{-1, 0, 0, 0};                      // variant -1: choose per call
+    patdnn_config_t cfg{-1, 0, 0, 1};                      // variant -1: choose per call
 
     ~patdnn_layer()
     {
@@ -204,8 +204,9 @@ patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const Conv
     if (vi < 0 || vi >= num_tiled_variants()) return fail(PATDNN_EINVAL, "no such variant");
     const TiledVariant& v = tiled_variant(vi);
     if (!variant_fits_layer(h, v)) return fail(PATDNN_EUNSUPPORTED, "variant cannot run this layer");
-    if (v.experimental && !experimental_allowed())
-        return fail(PATDNN_EUNSUPPORTED, "experimental variant: set PATDNN_EXPERIMENTAL=1 to run it");
+    if ((v.experimental || c.ksplit > 1) && !experimental_allowed())
+        return fail(PATDNN_EUNSUPPORTED, "experimental variant / ksplit: set PATDNN_EXPERIMENTAL=1 to run it");
+    if (c.ksplit > 1 && v.dense) return fail(PATDNN_EUNSUPPORTED, "ksplit is for sparse variants");
     int32_t ck = c.ck, waves = c.waves;
     if (!resolve_tiled_params(h, v, s, ck, waves))
         return fail(PATDNN_EUNSUPPORTED, "launch parameters outside the variant's limits");
@@ -217,7 +218,8 @@ patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const Conv
     t = &it->second->dev;
     DevTiled dt = *t;
     if (v.dense) { dt.ck = ck; dt.num_chunks = (s.c_in + ck - 1) / ck; }
-    hipError_t e = v.launch(dt, s, in, bias, out, waves, stream);
+    if (c.ksplit > dt.num_chunks) return fail(PATDNN_EUNSUPPORTED, "ksplit exceeds the number of channel chunks");
+    hipError_t e = v.launch(dt, s, in, bias, out, waves, c.ksplit, stream);
     return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching a tiled kernel");
 }
 
@@ -228,9 +230,9 @@ patdnn_config_t default_config(patdnn_layer* h, const ConvShape& s)
         const TiledVariant& v = tiled_variant(vi);
         if (!variant_selectable(h, v)) continue;
         int32_t ck = 0, waves = 0;
-        if (resolve_tiled_params(h, v, s, ck, waves)) return patdnn_config_t{vi + 1, ck, waves, 0};
+        if (resolve_tiled_params(h, v, s, ck, waves)) return patdnn_config_t{vi + 1, ck, waves, 1};
     }
-    return patdnn_config_t{PATDNN_VARIANT_FKW, 0, 0, 0};
+    return patdnn_config_t{PATDNN_VARIANT_FKW, 0, 0, 1};
 }
 
 }  // namespace
@@ -419,7 +421,7 @@ patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
 {
     if (!h || !cfg) return fail(PATDNN_EINVAL, "handle / cfg is NULL");
     if (cfg->variant < 0) {               // back to automatic choice
-        h->cfg = patdnn_config_t{-1, 0, 0, 0};
+        h->cfg = patdnn_config_t{-1, 0, 0, 1};
         return PATDNN_OK;
     }
     if (cfg->variant > num_tiled_variants()) return fail(PATDNN_EINVAL, "no such variant");
@@ -428,8 +430,10 @@ patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
         if (!variant_fits_layer(h, v)) return fail(PATDNN_EUNSUPPORTED, "variant cannot run this layer");
         if (v.experimental && h->on_device && !experimental_allowed())
             return fail(PATDNN_EUNSUPPORTED, "experimental variant: set PATDNN_EXPERIMENTAL=1 to run it");
-        if (cfg->ck < 0 || cfg->waves < 0 || cfg->waves > kMaxWaves)
-            return fail(PATDNN_EINVAL, "ck / waves out of range");
+        if (cfg->ck < 0 || cfg->waves < 0 || cfg->waves > kMaxWaves || cfg->ksplit < 0 || cfg->ksplit > 64)
+            return fail(PATDNN_EINVAL, "ck / waves / ksplit out of range");
+        if (cfg->ksplit > 1 && (v.dense || (h->on_device && !experimental_allowed())))
+            return fail(PATDNN_EUNSUPPORTED, "ksplit: sparse variants only, and PATDNN_EXPERIMENTAL=1");
         const int min_waves = (v.stage_elems + 64 * v.max_slots - 1) / (64 * v.max_slots);
         if (cfg->waves && cfg->waves < min_waves)
             return fail(PATDNN_EUNSUPPORTED, "too few wavefronts to stage a tile");
@@ -437,7 +441,7 @@ patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
             return fail(PATDNN_EUNSUPPORTED, "ck exceeds the LDS budget");
     }
     h->cfg = *cfg;
-    h->cfg.reserved = 0;
+    if (h->cfg.ksplit < 1 || cfg->variant <= 0) h->cfg.ksplit = 1;
     if (cfg->variant > 0) {
         const TiledVariant& v = tiled_variant(cfg->variant - 1);
         if (h->cfg.ck == 0) h->cfg.ck = default_ck(v, h->L.desc.c_in);
@@ -475,7 +479,7 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
     const int wave_opts[] = {1, 2, 4, 8};
     for (int vi = 0; vi < num_tiled_variants(); ++vi) {
         const TiledVariant& v = tiled_variant(vi);
-        if (!variant_selectable(h, v)) continue;
+        if (!(variant_selectable(h, v) || (experimental_allowed() && variant_fits_layer(h, v)))) continue;
         const int groups = (s.c_out + v.G - 1) / v.G;
         for (int ck : ck_opts)
             for (int waves : wave_opts) {
@@ -483,13 +487,18 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
                 if (w2 > 1 && w2 / 2 >= groups) continue;      // mostly idle wavefronts
                 if (!resolve_tiled_params(h, v, s, ck2, w2)) continue;
                 if (ensure_tiled(h, vi, ck2, nullptr) != PATDNN_OK) continue;
-                patdnn_config_t c{vi + 1, ck2, w2, 0};
-                bool dup = false;
-                for (const auto& o : cands) dup |= (o.variant == c.variant && o.ck == c.ck && o.waves == c.waves);
-                if (!dup) cands.push_back(c);
+                // input-channel slices only when experimental code paths are allowed
+                const int num_chunks = (s.c_in + ck2 - 1) / ck2;
+                for (int ks = 1; ks <= (experimental_allowed() && !v.dense ? 4 : 1) && ks <= num_chunks; ++ks) {
+                    patdnn_config_t c{vi + 1, ck2, w2, ks};
+                    bool dup = false;
+                    for (const auto& o : cands)
+                        dup |= (o.variant == c.variant && o.ck == c.ck && o.waves == c.waves && o.ksplit == c.ksplit);
+                    if (!dup) cands.push_back(c);
+                }
             }
     }
-    cands.push_back(patdnn_config_t{PATDNN_VARIANT_FKW, 0, 0, 0});
+    cands.push_back(patdnn_config_t{PATDNN_VARIANT_FKW, 0, 0, 1});
 
     hipEvent_t e0, e1;
     hipError_t e;

@@ -30,6 +30,7 @@ def main(argv=None) -> int:
     ap.add_argument("--variants", type=_ints, default=None, help="variant numbers (default: all that fit)")
     ap.add_argument("--ck", type=_ints, default=[4, 8, 16])
     ap.add_argument("--waves", type=_ints, default=[2, 4, 8])
+    ap.add_argument("--ksplit", type=_ints, default=[1], help="input-channel slices (>1 needs PATDNN_EXPERIMENTAL=1)")
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--json", action="store_true")
     args = ap.parse_args(argv)
@@ -56,11 +57,12 @@ def main(argv=None) -> int:
     variants = args.variants if args.variants is not None else list(range(B.patdnn_num_variants()))
     for v in variants:
         name = B.patdnn_variant_name(v)
-        combos = [(0, 0)] if v == B.PATDNN_VARIANT_FKW else [(c, w) for c in args.ck for w in args.waves]
-        for ck, waves in combos:
-            row = {"variant": v, "name": name, "ck": ck, "waves": waves}
+        combos = [(0, 0, 1)] if v == B.PATDNN_VARIANT_FKW else \
+            [(c, w, k) for c in args.ck for w in args.waves for k in args.ksplit]
+        for ck, waves, ksplit in combos:
+            row = {"variant": v, "name": name, "ck": ck, "waves": waves, "ksplit": ksplit}
             try:
-                L.set_config(v, ck, waves)
+                L.set_config(v, ck, waves, ksplit)
                 L.conv2d(x, bias, out, relu=True)
                 torch.cuda.synchronize()
             except B.PatdnnError as e:
@@ -79,7 +81,7 @@ def main(argv=None) -> int:
             row.update(status="ok", ms=round(ms, 4), nz_tflops=round(nz / ms / 1e9, 2))
             rows.append(row)
             if not args.json:
-                print(f"{spec.name} {spec.c_in}->{spec.c_out}@{spec.h} n={spec.n} {name} ck={ck} waves={waves}: "
+                print(f"{spec.name} {spec.c_in}->{spec.c_out}@{spec.h} n={spec.n} {name} ck={ck} waves={waves} ksplit={ksplit}: "
                       f"{ms:.4f} ms  {nz / ms / 1e9:.2f} TFLOP/s nz", flush=True)
     L.close()
     if args.json:

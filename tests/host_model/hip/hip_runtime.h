@@ -68,6 +68,22 @@ namespace patdnn { extern float lds[]; }
 inline void __syncthreads() { pthread_barrier_wait(&hostmodel::state().barrier); }
 inline int min(int a, int b) { return a < b ? a : b; }
 
+// hardware fp32 atomic add: workgroups run one after another here and the lanes of a
+// workgroup add to distinct elements, so a locked add is enough
+inline float unsafeAtomicAdd(float* p, float v)
+{
+    hostmodel::State& st = hostmodel::state();
+    if (p < st.out || p >= st.out + st.out_floats) {
+        hostmodel::fail("atomic add outside the output tensor", p - st.out);
+        return 0.0f;
+    }
+    pthread_mutex_lock(&st.lock);
+    const float old = *p;
+    *p = old + v;
+    pthread_mutex_unlock(&st.lock);
+    return old;
+}
+
 #define __builtin_amdgcn_readfirstlane(x) (x)
 #define __builtin_amdgcn_s_waitcnt(x) ((void)0)
 
@@ -108,8 +124,8 @@ inline void __builtin_amdgcn_raw_ptr_buffer_load_lds(__amdgpu_buffer_rsrc_t r, f
 }
 
 // ---- launch: workgroups one after another, one OS thread per GPU thread
-template <class Args>
-void hostmodel_launch(void (*kernel)(Args), dim3 grid, dim3 block, size_t lds_bytes, const Args& args)
+template <class... Args>
+void hostmodel_launch(void (*kernel)(Args...), dim3 grid, dim3 block, size_t lds_bytes, Args... args)
 {
     using namespace hostmodel;
     State& st = state();
@@ -117,8 +133,9 @@ void hostmodel_launch(void (*kernel)(Args), dim3 grid, dim3 block, size_t lds_by
     st.lds_floats = lds_bytes / 4;
     gridDim = grid;
     blockDim = block;
+    for (unsigned by = 0; by < grid.y; ++by)
     for (unsigned b = 0; b < grid.x; ++b) {
-        blockIdx = dim3(b);
+        blockIdx = dim3(b, by);
         const uint32_t poison = 0x7FC0DEADu;                 // NaN: reading unstaged LDS shows in the output
         for (size_t i = 0; i < kLdsFloats; ++i) std::memcpy(&patdnn::lds[i], &poison, 4);
         pthread_barrier_init(&st.barrier, nullptr, block.x);
@@ -126,14 +143,14 @@ void hostmodel_launch(void (*kernel)(Args), dim3 grid, dim3 block, size_t lds_by
         for (unsigned t = 0; t < block.x; ++t)
             threads.emplace_back([=]() {
                 threadIdx = dim3(t);
-                kernel(args);
+                kernel(args...);
             });
         for (auto& th : threads) th.join();
         pthread_barrier_destroy(&st.barrier);
     }
 }
-#define hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, args) \
-    hostmodel_launch(kernel, grid, block, lds_bytes, args)
+#define hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, ...) \
+    hostmodel_launch(kernel, grid, block, lds_bytes, __VA_ARGS__)
 
 // ---- the step interpreter, walked in C++ (one lane)
 struct HostmodelGeo {

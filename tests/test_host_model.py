@@ -72,7 +72,7 @@ def _build_hostmodel(build, edit=None):
     L = ctypes.CDLL(str(lib))
     L.hostmodel_run.restype = ctypes.c_long
     L.hostmodel_run.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p] * 4 + [ctypes.c_int] * 10 + \
-                               [ctypes.c_void_p] * 3 + [ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
+                               [ctypes.c_void_p] * 3 + [ctypes.c_int, ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
     return L
 
 
@@ -81,7 +81,7 @@ def hostmodel(tmp_path_factory):
     return _build_hostmodel(tmp_path_factory.mktemp("hostmodel"))
 
 
-def _run(hostmodel, v, t, x, bias, pad, stride, relu, waves, c_out, w9=None):
+def _run(hostmodel, v, t, x, bias, pad, stride, relu, waves, c_out, w9=None, ksplit=1):
     n, c_in, h, w = x.shape
     ho, wo = (h + 2 * pad - 3) // stride + 1, (w + 2 * pad - 3) // stride + 1
     guard = 1024
@@ -94,7 +94,7 @@ def _run(hostmodel, v, t, x, bias, pad, stride, relu, waves, c_out, w9=None):
     errs = hostmodel.hostmodel_run(v - 1, t["G"], t["num_groups"], t["ck"], t["num_chunks"],
                                    ptr(t["slot_channel"]), ptr(t.get("chunk_ptr")), ptr(t.get("steps")), ptr(w9),
                                    n, c_in, c_out, h, w, ho, wo, stride, pad, int(relu), ptr(x), ptr(bias),
-                                   out.ctypes.data, waves, msg, 512)
+                                   out.ctypes.data, waves, ksplit, msg, 512)
     assert errs == 0, msg.value.decode()
     assert (buf[:guard] == 777.0).all() and (buf[-guard:] == 777.0).all(), "write outside the output tensor"
     return out.reshape(n, c_out, ho, wo)
@@ -130,12 +130,13 @@ def test_every_sparse_variant_on_the_host_model(hostmodel, oracle, case):
             continue
         lds_per_channel = hostmodel.hostmodel_variant_lds_floats(v - 1)
         min_waves = -(-lds_per_channel // (64 * 16))        # enough staging slots for any compiled variant
-        got = _run(hostmodel, v, t, x, bias, case["pad"], stride, True, max(case["waves"], min_waves, 3),
-                   case["c_out"])
-        assert not np.isnan(got).any(), (B.patdnn_variant_name(v), "output element never written or unstaged LDS read")
-        err = float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
-        print(f"  {B.patdnn_variant_name(v)}: rel_err={err:.2e}")
-        assert err <= TOL, (B.patdnn_variant_name(v), err)
+        for ksplit in (1, min(3, t["num_chunks"])):
+            got = _run(hostmodel, v, t, x, bias, case["pad"], stride, True, max(case["waves"], min_waves, 3),
+                       case["c_out"], ksplit=ksplit)
+            assert not np.isnan(got).any(), (B.patdnn_variant_name(v), "output element never written or unstaged LDS read")
+            err = float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
+            print(f"  {B.patdnn_variant_name(v)} ksplit={ksplit}: rel_err={err:.2e}")
+            assert err <= TOL, (B.patdnn_variant_name(v), ksplit, err)
         seen += 1
     L.close()
     assert seen >= 2
@@ -147,8 +148,8 @@ def test_host_model_catches_planted_mistakes(tmp_path, oracle, plant):
         "staging column": lambda t: t.replace("const int ix = bxi * TGX * PC * S - a.pad + x;",
                                               "const int ix = bxi * TGX * PC * S - a.pad + x + 1;"),
         "epilogue guard": lambda t: t.replace("if (oy < a.ho && ox < a.wo) dst", "if (ox < a.wo) dst"),
-        "lane offset": lambda t: t.replace("const int lane_off = lb * PITCH + gx * PC * S;",
-                                           "const int lane_off = lb * PITCH + gx * PC * S + GEO::ROWP * 3;"),
+        "lane offset": lambda t: t.replace("lane_ok ? lb * PITCH + gx * PC * S : 0;",
+                                           "lane_ok ? lb * PITCH + gx * PC * S + GEO::ROWP * 3 : 0;"),
     }
     broken = _build_hostmodel(tmp_path, edits[plant])
     with pytest.raises(AssertionError):

@@ -61,7 +61,8 @@ def _model_conv(t, x, bias, pad, relu, stats):
     lds = np.zeros(2 * ck * TILEP, np.uint32)
     lane = np.arange(64)
     lb, gx = lane // TGX, lane % TGX
-    lane_off = lb * PITCH + gx * PC * S
+    lane_ok = lb < NB                      # TGX = 7: the 64th lane has no band
+    lane_off = np.where(lane_ok, lb * PITCH + gx * PC * S, 0)
     for tile in range(-(-num_bands // NB)):
         band0 = tile * NB
         for g in range(t["num_groups"]):
@@ -107,7 +108,7 @@ def _model_conv(t, x, bias, pad, relu, stats):
             # epilogue
             for ln in range(64):
                 band = band0 + lb[ln]
-                if band >= num_bands:
+                if not lane_ok[ln] or band >= num_bands:
                     continue
                 bxi, byi, img = band % bx, (band // bx) % by, band // (bx * by)
                 for s in range(G):
