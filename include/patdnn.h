@@ -184,8 +184,10 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
  * laid out for this GPU), for inspection and round-trip tests.  `ck` as in
  * patdnn_config_t (0 = the variant's default).  The layout is built if the handle
  * does not hold it yet.
- *   A group is `G` consecutive filters of the reordered layer; `slot_channel` gives
- *   the original output channel of each (group, slot), -1 for an unused slot.
+ *   A group is `G` filters that one wavefront computes; `slot_channel` gives the
+ *   original output channel of each (group, slot), -1 for an unused slot.  Filters are
+ *   assigned so that the groups carry equal work in every chunk (section 5.2: equal work
+ *   for the units that wait for each other).
  *   Per group and per chunk of `ck` input channels, the low 28 bits of `chunk_ptr`
  *   give the first step; a step is 24 dwords and all its kernels read ONE input
  *   channel.  A kernel's code offset is

@@ -207,13 +207,71 @@ void build_tiled(const LayerHost& L, const TiledParams& prm, Tiled& T)
     auto float_bits = [](float v) { uint32_t u; std::memcpy(&u, &v, 4); return u; };
     std::vector<Step> plan;
 
+    // ---- which filters share a group.  The wavefronts of a workgroup (consecutive groups)
+    // meet at a barrier after every chunk of input channels, so what has to be equal is the
+    // work of the groups chunk by chunk - the purpose the paper's filter reorder serves for
+    // the threads of a block (section 5.2).  Filters are dealt out longest first, each to
+    // the group with a free slot whose per-chunk load stays flattest (sum of squares), then
+    // pairs of filters are swapped between groups while that improves.  Dense layers have
+    // equal filters and keep the stored order.
+    std::vector<int32_t> members((size_t)T.num_groups * G, -1);    // [group][slot] -> FKW position
+    if (L.dense) {
+        for (int r = 0; r < c_out; ++r) members[r] = c_out - 1 - r;
+    } else {
+        const int nc = T.num_chunks, ng = T.num_groups;
+        std::vector<int32_t> fc((size_t)c_out * nc, 0);             // kernels of a filter per chunk
+        for (int s = 0; s < c_out; ++s)
+            for (int32_t k = f.offset[s]; k < f.offset[s + 1]; ++k) ++fc[(size_t)s * nc + f.index[k] / prm.ck];
+        std::vector<int64_t> load((size_t)ng * nc, 0);
+        std::vector<int32_t> fill(ng, 0), group_of(c_out, 0);
+        auto delta_sq = [&](int g, const int32_t* add, const int32_t* sub) {
+            int64_t d = 0;                                           // change of sum(load^2) of group g
+            for (int c = 0; c < nc; ++c) {
+                const int64_t a = load[(size_t)g * nc + c], b = a + add[c] - (sub ? sub[c] : 0);
+                d += b * b - a * a;
+            }
+            return d;
+        };
+        for (int r = 0; r < c_out; ++r) {
+            const int s = c_out - 1 - r;                             // FKW order ascends in length
+            int best = -1;
+            int64_t best_d = 0;
+            for (int g = 0; g < ng; ++g) {
+                if (fill[g] >= G) continue;
+                const int64_t d = delta_sq(g, &fc[(size_t)s * nc], nullptr);
+                if (best < 0 || d < best_d) { best = g; best_d = d; }
+            }
+            members[(size_t)best * G + fill[best]++] = s;
+            group_of[s] = best;
+            for (int c = 0; c < nc; ++c) load[(size_t)best * nc + c] += fc[(size_t)s * nc + c];
+        }
+        // bounded improvement by swaps; a fixed linear congruential sequence picks the pairs
+        uint64_t lcg = 0x9E3779B97F4A7C15ull;
+        const long attempts = std::min<long>(200000, 200l * c_out);
+        for (long it = 0; it < attempts && ng > 1; ++it) {
+            lcg = lcg * 6364136223846793005ull + 1442695040888963407ull;
+            const int ia = (int)((lcg >> 33) % (uint64_t)members.size());
+            lcg = lcg * 6364136223846793005ull + 1442695040888963407ull;
+            const int ib = (int)((lcg >> 33) % (uint64_t)members.size());
+            const int ga = ia / G, gb = ib / G, sa = members[ia], sb = members[ib];
+            if (ga == gb || sa < 0 || sb < 0) continue;
+            const int32_t* fa = &fc[(size_t)sa * nc];
+            const int32_t* fb = &fc[(size_t)sb * nc];
+            if (delta_sq(ga, fb, fa) + delta_sq(gb, fa, fb) >= 0) continue;
+            for (int c = 0; c < nc; ++c) {
+                load[(size_t)ga * nc + c] += fb[c] - fa[c];
+                load[(size_t)gb * nc + c] += fa[c] - fb[c];
+            }
+            std::swap(members[ia], members[ib]);
+        }
+    }
+
     std::vector<Entry> ent;
     for (int g = 0; g < T.num_groups; ++g) {
         ent.clear();
         for (int slot = 0; slot < G; ++slot) {
-            const int r = g * G + slot;               // rank among filters, longest first
-            if (r >= c_out) break;
-            const int s = c_out - 1 - r;              // FKW position (lengths ascend there)
+            const int s = members[(size_t)g * G + slot];   // FKW position of the filter
+            if (s < 0) continue;
             T.slot_channel[(size_t)g * G + slot] = f.reorder[s];
             T.group_kernels[g] += f.offset[s + 1] - f.offset[s];
             const int32_t* st = &f.stride[(size_t)s * (P + 1)];

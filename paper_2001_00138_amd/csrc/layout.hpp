@@ -49,8 +49,9 @@ struct Fkw {
 };
 
 // ---------------------------------------------------------------------------
-// Tiled layout for one kernel variant.  Filters are taken G at a time from the FKR
-// order, longest first.  Sparse layers: per filter group and per chunk of `ck` input
+// Tiled layout for one kernel variant.  G filters share a filter group (one wavefront);
+// which ones is chosen so that the groups have equal work in every chunk of input
+// channels (encoder.cpp).  Sparse layers: per filter group and per chunk of `ck` input
 // channels, a sequence of fixed-size steps (kStepDwords = 24 dwords) that the kernel's
 // interpreter executes in order.  All kernels of a step read ONE input channel.
 // Kernels are listed channel-major so that one window load serves every kernel of the
