@@ -475,8 +475,10 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
     hipStream_t stream = static_cast<hipStream_t>(stream_);
 
     std::vector<patdnn_config_t> cands;
-    const int ck_opts[] = {4, 8, 16, 32};
-    const int wave_opts[] = {1, 2, 4, 8};
+    // 9 and 12 are the largest chunk sizes that still fit three / two workgroups of the
+    // 7x1 tiles into one CU's LDS; 3 and 6 wavefronts give workgroup counts in between
+    const int ck_opts[] = {4, 6, 8, 9, 12, 16, 24, 32};
+    const int wave_opts[] = {1, 2, 3, 4, 6, 8};
     for (int vi = 0; vi < num_tiled_variants(); ++vi) {
         const TiledVariant& v = tiled_variant(vi);
         if (!(variant_selectable(h, v) || (experimental_allowed() && variant_fits_layer(h, v)))) continue;
