@@ -197,12 +197,13 @@ def main() -> int:
     # beside the throughput number, never instead of it)
     latency = None
     if not args.no_latency and args.config == 5:
-        try:
+        def stack_latency(cfg_no):
+            """One image through every layer of a configuration, launches back to back."""
             one = []
-            for li in range(len(wl.config_layers(2))):
-                d1 = wl.gen_layer(2, li, with_input=False)
+            for li in range(len(wl.config_layers(cfg_no))):
+                d1 = wl.gen_layer(cfg_no, li, n=1, with_input=False)
                 s1 = d1["spec"]
-                x1 = torch.from_numpy(wl.gen_input_image(s1, 2, li, 0)[None]).cuda()
+                x1 = torch.from_numpy(wl.gen_input_image(s1, cfg_no, li, 0)[None]).cuda()
                 L1 = B.Layer.from_workload(d1)
                 b1 = torch.from_numpy(d1["bias"]).cuda()
                 o1 = torch.empty(L1.output_shape(1, s1.h, s1.w), dtype=torch.float32, device="cuda")
@@ -222,14 +223,21 @@ def main() -> int:
             e1.record(stream)
             torch.cuda.synchronize()
             ms1 = e0.elapsed_time(e1) / reps
-            nz1 = sum(wl.nz_flops(s1, k1) for _, _, _, _, s1, k1 in one)
-            latency = {"workload": wl.CONFIG_NAMES[2], "ms_per_image": round(ms1, 4),
-                       "nz_gflops": round(nz1 / (ms1 * 1e-3) / 1e9, 1),
-                       "note": "13 launches back to back on one stream, launch gaps included"}
+            nz1 = sum(wl.nz_flops(s1, k1, n=1) for _, _, _, _, s1, k1 in one)
+            by1 = sum(wl.algorithmic_bytes(s1, k1, n=1) for _, _, _, _, s1, k1 in one)
+            kernels = sorted({variant_name(L1.get_config()) for L1, *_ in one})
             for L1, *_ in one:
                 L1.close()
-        except Exception as exc:        # the throughput line must not depend on this leg
-            latency = {"error": f"{type(exc).__name__}: {exc}"}
+            return {"workload": wl.CONFIG_NAMES[cfg_no], "layers": len(one), "ms_per_image": round(ms1, 4),
+                    "nz_gflops": round(nz1 / (ms1 * 1e-3) / 1e9, 1),
+                    "alg_gbps": round(by1 / (ms1 * 1e-3) / 1e9, 1), "kernels": kernels}
+
+        latency = {"note": "one image, all layers launched back to back on one stream, launch gaps included"}
+        for key, cfg_no in (("vgg16", 2), ("resnet50_3x3", 3), ("mobilenet_v2_depthwise", 4)):
+            try:
+                latency[key] = stack_latency(cfg_no)
+            except Exception as exc:        # the throughput line must not depend on this leg
+                latency[key] = {"error": f"{type(exc).__name__}: {exc}"}
 
     # ------------------------------------------------------------------ dense comparison (same shapes)
     dense_cmp = None
