@@ -306,6 +306,13 @@ patdnn_status_t patdnn_conv2d(patdnn_handle_t h, const float* input, int32_t n, 
     if (!h->on_device) return fail(PATDNN_EHIP, "handle was encoded with PATDNN_HOST_ONLY");
     if (n == 0) return PATDNN_OK;
     if (!input || !output) return fail(PATDNN_EINVAL, "input / output is NULL");
+    {
+        const char* in_lo = reinterpret_cast<const char*>(input);
+        const char* in_hi = in_lo + 4ull * (size_t)n * s.c_in * s.h * s.w;
+        const char* out_lo = reinterpret_cast<const char*>(output);
+        const char* out_hi = out_lo + 4ull * (size_t)n * s.c_out * s.ho * s.wo;
+        if (in_lo < out_hi && out_lo < in_hi) return fail(PATDNN_EINVAL, "output overlaps input");
+    }
     s.relu = fuse_relu ? 1 : 0;
     patdnn_config_t c = h->cfg;
     if (c.variant < 0) c = default_config(h, s);

@@ -162,6 +162,13 @@ def test_degenerate_layers(torch, oracle):
     L = B.Layer.from_workload(d)
     out = L.conv2d(torch.empty((0, 12, 10, 10), device="cuda"), None)
     assert tuple(out.shape) == (0, 20, 10, 10)
+    # an output that overlaps the input is refused before anything is launched
+    both = torch.zeros(2 * 12 * 10 * 10 + 2 * 20 * 10 * 10, device="cuda")
+    xin = both[:2 * 12 * 10 * 10].view(2, 12, 10, 10)
+    bad_out = both[100:100 + 2 * 20 * 10 * 10].view(2, 20, 10, 10)
+    with pytest.raises(B.PatdnnError) as e:
+        L.conv2d(xin, None, bad_out)
+    assert e.value.status == B.PATDNN_EINVAL
     L.close()
 
 
