@@ -12,7 +12,9 @@ specialisation
 
 whose body is ONE inline-assembly statement, hand-scheduled for gfx950.
 MODE bit 0: two sets of window registers; bit 1: threaded dispatch; bit 2: the window
-lives in fixed vector registers and is read from LDS two floats at a time.
+lives in fixed vector registers and is read from LDS two floats at a time; bit 3: the
+staged channel is laid out band by band (bank-conflict-free window reads) instead of
+row by row.
 
 The encoder turns the kept kernels of one filter group and one chunk of staged input
 channels into a sequence of fixed-size *steps* (24 dwords each); all kernels of a step
@@ -98,13 +100,23 @@ def pow2_at_least(n):
 
 def geometry(G, PR, PC, S, TGX, MODE):
     WR, WC = (PR - 1) * S + 3, (PC - 1) * S + 3
-    pitch = (64 // TGX) * ((TGX * PC - 1) * S + 3)     # floats per staged row: the bands side by side
+    band_cols = (TGX * PC - 1) * S + 3
+    if MODE & 8:
+        # band-major LDS layout: a band's window rows follow each other; bands start
+        # (lanes-per-band step) mod 32 banks apart (the kernel's Geo computes the same)
+        pitch = band_cols
+        band = WR * band_cols
+        band_stride = band + ((TGX * PC * S) % 32 - band % 32 + 32) % 32
+    else:
+        pitch = (64 // TGX) * band_cols                # floats per staged row: the bands side by side
+        band_stride = band_cols
     nacc = PR * PC
     threaded = bool(MODE & 2)
     tail = 7 if threaded else 1                        # 4-byte scalar instructions after the FMAs
     block_bytes = pow2_at_least(4 * (4 * nacc + tail))
     num_ctrl = T_NUM_CTRL if threaded else C_NUM_CTRL
-    return dict(WR=WR, WC=WC, pitch=pitch, nacc=nacc, nwin=WR * WC, block_bytes=block_bytes,
+    return dict(WR=WR, WC=WC, pitch=pitch, band_stride=band_stride, band_cols=band_cols,
+                band_major=bool(MODE & 8), nacc=nacc, nwin=WR * WC, block_bytes=block_bytes,
                 table_off=num_ctrl * CTRL_SLOT, sets=2 if MODE & 1 else 1, threaded=threaded,
                 wide=bool(MODE & 4),
                 records=T_RECORDS if threaded else C_RECORDS, ctrl_bytes=CTRL_SLOT,

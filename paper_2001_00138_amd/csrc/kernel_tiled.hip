@@ -54,13 +54,22 @@ struct Geo {
     static constexpr int WR = (PR - 1) * S + 3;         // window (= staged band) rows
     static constexpr int WC = (PC - 1) * S + 3;         // window columns per lane
     static constexpr int PITCH = (TGX * PC - 1) * S + 3;  // staged band columns
-    // LDS layout of one staged channel: [window row][band][column] - the same row of
-    // the NB bands side by side, so that 64 consecutive LDS dwords (what one staging
+    // LDS layout of one staged channel.
+    // Row-interleaved (MODE bit 3 clear): [window row][band][column] - the same row of the
+    // NB bands side by side, so that 64 consecutive LDS dwords (what one staging
     // instruction of a wavefront fills) come from a short run of one image row when the
-    // bands are neighbours in x
-    static constexpr int ROWP = NB * PITCH;             // floats per staged row
+    // bands are neighbours in x.
+    // Band-major (MODE bit 3 set): [band][window row][column], bands BANDP floats apart
+    // with BANDP = lanes-per-band step (mod 32), so that the lanes of half a wavefront
+    // fall on 32 different LDS banks when they read the same window element.
+    static constexpr bool BAND_MAJOR = (MODE & 8) != 0;
+    static constexpr int ROWP = NB * PITCH;             // floats per staged row (row-interleaved)
+    static constexpr int BAND = WR * PITCH;             // floats of one band
+    static constexpr int BANDP = BAND + ((TGX * PC * S) % 32 - BAND % 32 + 32) % 32;
+    static constexpr int RSTRIDE = BAND_MAJOR ? PITCH : ROWP;    // between a lane's window rows
+    static constexpr int BSTRIDE = BAND_MAJOR ? BANDP : PITCH;   // between bands
     // floats per staged channel; a multiple of 64 (one staging instruction = 64 dwords)
-    static constexpr int TILEP = (WR * ROWP + 63) / 64 * 64;
+    static constexpr int TILEP = ((BAND_MAJOR ? NB * BANDP : WR * ROWP) + 63) / 64 * 64;
     static constexpr int NACC = PR * PC;
 };
 
@@ -127,9 +136,20 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     for (int k = 0; k < GEO::MAXSLOTS; ++k) {
         const int e = tid + k * nthreads;
         voff[k] = ~0u;
-        const int q = e / GEO::ROWP, rem = e - q * GEO::ROWP;
+        int q, b, x;
+        if constexpr (GEO::BAND_MAJOR) {
+            b = e / GEO::BANDP;
+            const int rem = e - b * GEO::BANDP;
+            q = rem / PITCH;
+            x = rem - q * PITCH;
+            if (b >= NB) q = WR;                        // beyond the last band: padding
+        } else {
+            q = e / GEO::ROWP;
+            const int rem = e - q * GEO::ROWP;
+            b = rem / PITCH;
+            x = rem - b * PITCH;
+        }
         if (q < WR) {
-            const int b = rem / PITCH, x = rem - b * PITCH;
             const int band = band0 + b;
             if (band < a.num_bands) {
                 const int bxi = band % a.bx, t = band / a.bx;
@@ -178,7 +198,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
         oy0 = byi * PR;
         ox0 = (bxi * TGX + gx) * PC;
     }
-    const int lane_off = lane_ok ? lb * PITCH + gx * PC * S : 0;   // floats, inside one staged channel
+    const int lane_off = lane_ok ? lb * GEO::BSTRIDE + gx * PC * S : 0;   // floats, inside one staged channel
 
     float acc[G][GEO::NACC];
 #pragma unroll
@@ -213,7 +233,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
 #pragma unroll
                     for (int q = 0; q < WR; ++q)
 #pragma unroll
-                        for (int r = 0; r < WC; ++r) win[q * WC + r] = base[q * GEO::ROWP + r];
+                        for (int r = 0; r < WC; ++r) win[q * WC + r] = base[q * GEO::RSTRIDE + r];
                     const float* wp = a.w9 + ((size_t)group * a.c_in + (c0 + c)) * (G * 9);
 #pragma unroll
                     for (int s = 0; s < G; ++s)

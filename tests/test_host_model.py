@@ -148,8 +148,7 @@ def test_host_model_catches_planted_mistakes(tmp_path, oracle, plant):
         "staging column": lambda t: t.replace("const int ix = bxi * TGX * PC * S - a.pad + x;",
                                               "const int ix = bxi * TGX * PC * S - a.pad + x + 1;"),
         "epilogue guard": lambda t: t.replace("if (oy < a.ho && ox < a.wo) dst", "if (ox < a.wo) dst"),
-        "lane offset": lambda t: t.replace("lane_ok ? lb * PITCH + gx * PC * S : 0;",
-                                           "lane_ok ? lb * PITCH + gx * PC * S + GEO::ROWP * 3 : 0;"),
+        "lane offset": lambda t: t.replace("+ gx * PC * S : 0;", "+ gx * PC * S + GEO::ROWP * 3 : 0;"),
     }
     broken = _build_hostmodel(tmp_path, edits[plant])
     with pytest.raises(AssertionError):

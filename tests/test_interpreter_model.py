@@ -47,10 +47,10 @@ def _model_conv(t, x, bias, pad, relu, stats):
     G, PR, PC, S, TGX = t["G"], t["patch_rows"], t["patch_cols"], t["conv_stride"], t["lanes_x"]
     NB, WR, WC = 64 // TGX, geo["WR"], geo["WC"]
     PITCH = (TGX * PC - 1) * S + 3
-    ROWP = NB * PITCH
-    assert geo["pitch"] == ROWP
+    assert geo["band_cols"] == PITCH
+    RSTRIDE, BSTRIDE = geo["pitch"], geo["band_stride"]      # between window rows / between bands
     TILEP = t["lds_channel_bytes"] // 4
-    assert TILEP >= WR * ROWP and TILEP % 64 == 0
+    assert TILEP >= (WR - 1) * RSTRIDE + (NB - 1) * BSTRIDE + PITCH and TILEP % 64 == 0
     n, c_in, h, w = x.shape
     ho, wo = (h + 2 * pad - 3) // S + 1, (w + 2 * pad - 3) // S + 1
     c_out = int(t["slot_channel"].max()) + 1
@@ -62,7 +62,7 @@ def _model_conv(t, x, bias, pad, relu, stats):
     lane = np.arange(64)
     lb, gx = lane // TGX, lane % TGX
     lane_ok = lb < NB                      # TGX = 7: the 64th lane has no band
-    lane_off = np.where(lane_ok, lb * PITCH + gx * PC * S, 0)
+    lane_off = np.where(lane_ok, lb * BSTRIDE + gx * PC * S, 0)
     for tile in range(-(-num_bands // NB)):
         band0 = tile * NB
         for g in range(t["num_groups"]):
@@ -75,6 +75,7 @@ def _model_conv(t, x, bias, pad, relu, stats):
                 lds[cur:cur + ck * TILEP] = 0xFFC00000           # NaN pattern where nothing is staged
                 for c in range(cn):
                     ch = np.zeros((WR, NB, PITCH), np.float32)
+                    img_of = np.full(TILEP, 0xFFC00000, np.uint32)   # the channel as it lies in LDS
                     for b in range(NB):
                         band = band0 + b
                         if band >= num_bands:
@@ -87,8 +88,12 @@ def _model_conv(t, x, bias, pad, relu, stats):
                             ix = bxi * TGX * PC * S - pad + np.arange(PITCH)
                             ok = (ix >= 0) & (ix < w)
                             ch[q, b, ok] = x[img, c0 + c, iy, ix[ok]]
+                    for q in range(WR):
+                        for b in range(NB):
+                            o = q * RSTRIDE + b * BSTRIDE
+                            img_of[o:o + PITCH] = ch[q, b].view(np.uint32)
                     at = cur + c * TILEP
-                    lds[at:at + WR * ROWP] = ch.reshape(-1).view(np.uint32)
+                    lds[at:at + TILEP] = img_of
                 cp = int(t["chunk_ptr"][g, chunk])
                 wave = gcn_model.Wave(prog, t["steps"], lds)
                 for s in range(G):
