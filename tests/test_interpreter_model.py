@@ -129,13 +129,15 @@ def _model_conv(t, x, bias, pad, relu, stats):
     return out
 
 
-def _check(oracle, d, x, ck, pad=1, stride=1):
+def _check(oracle, d, x, ck, pad=1, stride=1, only=None):
     ref = oracle.conv2d(d["weights"], d["pattern_ids"], d["kernel_mask"], d["pattern_masks"], x,
                         d["bias"], stride=stride, pad=pad, relu=True)
     L = B.Layer(d["weights"], d["pattern_ids"], d["kernel_mask"], d["pattern_masks"], pad=pad,
                 stride=stride, host_only=True)
     seen = []
     for v in range(1, B.patdnn_num_variants()):
+        if only is not None and B.patdnn_variant_name(v) not in only:
+            continue
         try:
             t = L.export_tiled(v, ck)
         except B.PatdnnError as e:
@@ -181,6 +183,18 @@ def test_model_runs_ragged_layers(oracle, case):
     stride = case.get("stride", 1)
     seen = _check(oracle, d, x, case["ck"], pad=case["pad"], stride=stride)
     assert len(seen) >= (7 if stride == 1 else 2)
+
+
+def test_model_runs_long_streams(oracle):
+    """A 128 -> 128 layer at the paper's density (hundreds of steps per group, sixteen
+    chunks, both register-set parities many times over) on one variant of every
+    interpreter mode."""
+    d = wl.gen_layer(3, 4, with_input=False)           # 128 -> 128
+    x = wl.gen_input(d["spec"], 3, 4, 1)[:, :, :7, :14]
+    seen = _check(oracle, d, x, 8, only={
+        "t_g16_p7x1_s1_x16", "t_g16_p7x1_s1_x16_dw", "t_g16_p7x1_s1_x16_th", "t_g8_p7x2_s1_x8_thdw",
+        "t_g8_p7x2_s1_x8_thw", "t_g16_p7x1_s1_x7_th", "t_g16_p7x1_s1_x16_thb"})
+    assert len(seen) == 7
 
 
 def test_model_catches_planted_mistakes(oracle):
