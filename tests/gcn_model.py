@@ -41,11 +41,12 @@ def _is_inline_const(v: int) -> bool:
 class Program:
     """Decoded program: instruction list, address of each, label -> address."""
 
-    def __init__(self, lines: List[str]):
+    def __init__(self, lines: List[str], code_base: int = CODE_BASE):
         self.ins = []          # (mnemonic, [operands], address)
         self.at: Dict[int, int] = {}
         self.labels: Dict[str, int] = {}
-        pc = CODE_BASE
+        self.base = code_base  # a multiple of every alignment used
+        pc = code_base
         for raw in lines:
             line = raw.strip()
             if not line:
@@ -174,13 +175,13 @@ class Wave:
         """A computed jump may only land on the start of a block (every block start and
         the exit carry a label) or on the instruction after a call."""
         if target not in self.p.label_addresses and target not in self.return_points:
-            raise ModelError(f"computed jump to {target - CODE_BASE:#x}, which is not a block start")
+            raise ModelError(f"computed jump to {target - self.p.base:#x}, which is not a block start")
         return target
 
     # ---- execution
     def run(self, max_instructions: int = 50_000_000) -> None:
         p = self.p
-        pc = CODE_BASE
+        pc = p.base
         s = self.s
         while True:
             if pc == p.end:                              # fell off the end of the statement
@@ -188,7 +189,7 @@ class Wave:
                     raise ModelError("the statement ends with loads in flight")
                 return
             if pc not in p.at:
-                raise ModelError(f"jump into the middle of nowhere: {pc - CODE_BASE:#x}")
+                raise ModelError(f"jump into the middle of nowhere: {pc - p.base:#x}")
             op, a, addr, off, size = p.ins[p.at[pc]]
             nxt = pc + size
             self.executed += 1
@@ -203,14 +204,14 @@ class Wave:
             elif op == "ds_read_b32":
                 va = self.vreg(a[1]).astype(np.int64) + off
                 if (va % 4).any() or (va < 0).any() or (va + 4 > self.lds.size * 4).any():
-                    raise ModelError(f"LDS read out of the staged region at {addr - CODE_BASE:#x}")
+                    raise ModelError(f"LDS read out of the staged region at {addr - p.base:#x}")
                 if self.vkey(a[0]) in self.pending_v:
                     raise ModelError("two LDS reads in flight into one register")
                 self.pending_v[self.vkey(a[0])] = self.lds[va // 4].copy()
             elif op == "ds_read_b64":
                 va = self.vreg(a[1]).astype(np.int64) + off
                 if (va % 8).any() or (va < 0).any() or (va + 8 > self.lds.size * 4).any():
-                    raise ModelError(f"misaligned or out-of-range 64-bit LDS read at {addr - CODE_BASE:#x}")
+                    raise ModelError(f"misaligned or out-of-range 64-bit LDS read at {addr - p.base:#x}")
                 lo, hi = re.match(r"^v\[(\d+):(\d+)\]$", a[0]).groups()
                 if int(hi) != int(lo) + 1 or int(lo) % 2:
                     raise ModelError(f"bad 64-bit destination {a[0]}")

@@ -37,7 +37,10 @@ def _program(t):
         lines, geo = gen_dispatch.program(*key)
         assert geo["block_bytes"] == t["block_bytes"] and geo["table_off"] == t["table_off"]
         assert geo["ctrl_bytes"] == t["ctrl_bytes"] and geo["records"] == t["records"]
-        _programs[key] = (gcn_model.Program(lines), geo)
+        # odd keys are laid out just below a 4 GiB boundary, so that the table straddles it and
+        # the carry of every computed code address is exercised
+        base = gcn_model.CODE_BASE if len(_programs) % 2 == 0 else 0x7F00_FFFF_0000
+        _programs[key] = (gcn_model.Program(lines, base), geo)
     return _programs[key]
 
 
