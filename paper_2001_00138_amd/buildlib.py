@@ -33,7 +33,9 @@ def sparse_geometries():
             m = re.search(r"X\(\s*\w+\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(\d+)\s*,\s*(true|false)"
                           r"\s*,\s*\d+\s*,\s*(\d+)", line)
             if m and m.group(6) == "false":
-                geos.add(tuple(int(m.group(i)) for i in (1, 2, 3, 4, 5, 7)))
+                g = [int(m.group(i)) for i in (1, 2, 3, 4, 5, 7)]
+                g[5] &= 15          # MODE bit 4 belongs to the kernel; the interpreter is shared
+                geos.add(tuple(g))
     return sorted(geos)
 
 

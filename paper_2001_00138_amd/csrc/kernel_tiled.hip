@@ -215,15 +215,26 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
         c_first = chunk_first * a.ck;
         c_end = min(a.c_in, (int)((long long)a.num_chunks * (y + 1) / k) * a.ck);
     }
-    stage(c_first, lds3);
+    // MODE bit 4: ONE staging buffer (half the LDS, so twice the channels per chunk or more
+    // workgroups per CU); the chunk is loaded after everyone has left the previous one and
+    // the other workgroups of the CU cover the wait.  Otherwise two alternating buffers.
+    constexpr bool ONE_BUFFER = (GEO::MODE & 16) != 0;
+    if constexpr (!ONE_BUFFER) stage(c_first, lds3);
     for (int c0 = c_first, chunk = SPLITK ? chunk_first : 0; c0 < c_end; c0 += a.ck, ++chunk) {
         const int cn = min(a.ck, a.c_in - c0);
-        const int cur = ((SPLITK ? chunk - chunk_first : chunk) & 1) * buf_floats;
-        // chunk `chunk` has landed in this wavefront's view, and (barrier) in everyone's;
-        // everyone has also finished reading the other buffer
-        __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
-        __syncthreads();
-        if (c0 + a.ck < c_end) stage(c0 + a.ck, lds3 + (buf_floats - cur));
+        const int cur = ONE_BUFFER ? 0 : ((SPLITK ? chunk - chunk_first : chunk) & 1) * buf_floats;
+        if constexpr (ONE_BUFFER) {
+            __syncthreads();                      // everyone has finished reading the buffer
+            stage(c0, lds3);
+            __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+            __syncthreads();
+        } else {
+            // chunk `chunk` has landed in this wavefront's view, and (barrier) in everyone's;
+            // everyone has also finished reading the other buffer
+            __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+            __syncthreads();
+            if (c0 + a.ck < c_end) stage(c0 + a.ck, lds3 + (buf_floats - cur));
+        }
 
         if (group_ok) {
             if constexpr (GEO::DENSE) {
@@ -254,7 +265,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                 // control block that enters it
                 const unsigned cp = load_uniform(a.chunk_ptr, (size_t)group * a.num_chunks + chunk);
                 const unsigned start = cp & kChunkStepMask;
-                using Loop = StreamLoop<G, PR, PC, S, TGX, GEO::MODE>;
+                using Loop = StreamLoop<G, PR, PC, S, TGX, (GEO::MODE & 15)>;   // bit 4 is the kernel's, not the interpreter's
                 const unsigned lds_base =
                     (unsigned)(uintptr_t)(__attribute__((address_space(3))) float*)lds;
                 Loop::run(acc, lds_base + 4u * (unsigned)(cur + lane_off),
@@ -329,7 +340,7 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
     a.fgsets = (t.num_groups + waves - 1) / waves;
     const long long blocks = tiles * a.fgsets;
     if (bands > INT32_MAX || blocks > INT32_MAX) return hipErrorInvalidValue;
-    const size_t lds_bytes = 2 * (size_t)t.ck * GEO::TILEP * sizeof(float);     // two staging buffers
+    const size_t lds_bytes = ((GEO::MODE & 16) ? 1 : 2) * (size_t)t.ck * GEO::TILEP * sizeof(float);   // staging buffers
     static bool big_lds_allowed = false;
     if (lds_bytes > 64 * 1024 && !big_lds_allowed) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, false>),
@@ -371,13 +382,13 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
 #define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, MODE, EXPERIMENTAL)                    \
     using Geo_##name = Geo<G, PR, PC, S, TGX, DENSE, MAXSLOTS, MODE>;                      \
     using Stream_##name = std::conditional<DENSE, NoStream<G, PR, PC, S, TGX, MODE>,       \
-                                           StreamLoop<G, PR, PC, S, TGX, MODE>>::type;
+                                           StreamLoop<G, PR, PC, S, TGX, ((MODE) & 15)>>::type;
 PATDNN_VARIANTS
 #undef X
 
 static const TiledVariant kVariants[] = {
 #define X(name, G, PR, PC, S, TGX, DENSE, MAXSLOTS, MODE, EXPERIMENTAL)                    \
-    {#name, G, PR, PC, S, TGX, DENSE, ((MODE) & 1) != 0, ((MODE) & 2) != 0, EXPERIMENTAL != 0, MODE, \
+    {#name, G, PR, PC, S, TGX, DENSE, ((MODE) & 1) != 0, ((MODE) & 2) != 0, EXPERIMENTAL != 0, MODE, ((MODE) & 16) ? 1 : 2, \
      Geo_##name::TILEP, Geo_##name::TILEP,                                                 \
      MAXSLOTS, Stream_##name::kBlockBytes, Stream_##name::kTableOff, Stream_##name::kCtrlBytes, \
      Stream_##name::kRecords, &launch_tiled<Geo_##name>},

@@ -54,7 +54,8 @@ struct TiledVariant {
     bool double_window;   // two sets of window registers: the next channel's window loads early
     bool threaded;        // every code block jumps straight to the next kernel's block
     bool experimental;    // not yet measured on hardware: never chosen by default or by the tuner
-    int32_t mode;         // the interpreter's MODE bits (gen_dispatch.py)
+    int32_t mode;         // MODE bits: 0-3 the interpreter's (gen_dispatch.py), 4 one staging buffer
+    int32_t lds_buffers;  // staging buffers of `ck` channels each (1 or 2)
     int32_t lds_floats_per_channel;   // LDS floats one staged channel takes
     int32_t stage_elems;              // elements staged per channel (without bank padding)
     int32_t max_slots;                // staging elements per thread the kernel can hold

@@ -111,7 +111,7 @@ constexpr int kMaxWaves = 8;
 
 int default_ck(const TiledVariant& v, int c_in)
 {
-    const int max_ck = kMaxLdsBytes / (8 * v.lds_floats_per_channel);
+    const int max_ck = kMaxLdsBytes / (4 * v.lds_buffers * v.lds_floats_per_channel);
     return std::max(1, std::min(std::min(8, max_ck), c_in));
 }
 
@@ -125,7 +125,7 @@ bool resolve_tiled_params(const patdnn_layer* h, const TiledVariant& v, const Co
     if (min_waves > kMaxWaves) return false;
     if (waves <= 0) waves = std::max(min_waves, std::min(num_groups, 4));
     if (waves < min_waves || waves > kMaxWaves) return false;
-    const int max_ck = kMaxLdsBytes / (8 * v.lds_floats_per_channel);
+    const int max_ck = kMaxLdsBytes / (4 * v.lds_buffers * v.lds_floats_per_channel);
     if (max_ck < 1) return false;
     if (ck <= 0) ck = default_ck(v, s.c_in);
     if (ck < 1 || ck > max_ck) return false;
@@ -444,7 +444,7 @@ patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
         const int min_waves = (v.stage_elems + 64 * v.max_slots - 1) / (64 * v.max_slots);
         if (cfg->waves && cfg->waves < min_waves)
             return fail(PATDNN_EUNSUPPORTED, "too few wavefronts to stage a tile");
-        if (cfg->ck && cfg->ck * 8 * v.lds_floats_per_channel > kMaxLdsBytes)
+        if (cfg->ck && cfg->ck * 4 * v.lds_buffers * v.lds_floats_per_channel > kMaxLdsBytes)
             return fail(PATDNN_EUNSUPPORTED, "ck exceeds the LDS budget");
     }
     h->cfg = *cfg;
@@ -552,7 +552,7 @@ static patdnn_status_t find_tiled(patdnn_handle_t h, int32_t variant, int32_t ck
     if (ck < 0) return fail(PATDNN_EINVAL, "ck out of range");
     if (ck == 0) ck = default_ck(v, h->L.desc.c_in);
     ck = std::min(ck, h->L.desc.c_in);
-    if (ck * 8 * v.lds_floats_per_channel > kMaxLdsBytes) return fail(PATDNN_EUNSUPPORTED, "ck exceeds the LDS budget");
+    if (ck * 4 * v.lds_buffers * v.lds_floats_per_channel > kMaxLdsBytes) return fail(PATDNN_EUNSUPPORTED, "ck exceeds the LDS budget");
     try {
         patdnn_status_t st = ensure_tiled(h, vi, ck, nullptr);
         if (st != PATDNN_OK) return st;

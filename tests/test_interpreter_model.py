@@ -32,7 +32,7 @@ def _built():
 
 def _program(t):
     key = (t["G"], t["patch_rows"], t["patch_cols"], t["conv_stride"], t["lanes_x"],
-           t["mode"])
+           t["mode"] & 15)               # bit 4 (one staging buffer) is the kernel's, not the interpreter's
     if key not in _programs:
         lines, geo = gen_dispatch.program(*key)
         assert geo["block_bytes"] == t["block_bytes"] and geo["table_off"] == t["table_off"]
@@ -73,7 +73,7 @@ def _model_conv(t, x, bias, pad, relu, stats):
             for chunk in range(t["num_chunks"]):
                 c0 = chunk * ck
                 cn = min(ck, c_in - c0)
-                cur = (chunk & 1) * ck * TILEP
+                cur = 0 if t["mode"] & 16 else (chunk & 1) * ck * TILEP
                 # the staged chunk: [channel][window row][band][column], zero outside the image
                 lds[cur:cur + ck * TILEP] = 0xFFC00000           # NaN pattern where nothing is staged
                 for c in range(cn):
