@@ -247,6 +247,17 @@ patdnn_status_t patdnn_export_tiled(patdnn_handle_t h, int32_t variant, int32_t 
  */
 patdnn_status_t patdnn_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
 
+/*
+ * Device self-test behind the variants with threaded dispatch: checks on the current
+ * device that scalar relative moves (the instruction those variants use to fetch the
+ * next record, whose result becomes a jump address) behave as the generated code
+ * assumes.  Runs one tiny kernel the first time (allocates and frees 20 bytes,
+ * synchronises); later calls return the remembered result.  PATDNN_OK, or
+ * PATDNN_EUNSUPPORTED with the reason in patdnn_last_error(); the library refuses to
+ * build threaded layouts on a device that fails it.
+ */
+patdnn_status_t patdnn_selftest(void);
+
 void        patdnn_destroy(patdnn_handle_t h);          /* NULL is a no-op */
 const char* patdnn_status_string(patdnn_status_t s);
 const char* patdnn_last_error(void);

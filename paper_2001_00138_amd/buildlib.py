@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libpatdnn.so")
-SOURCES = ["patdnn_api.hip", "kernel_fkw.hip", "kernel_tiled.hip", "copy_probe.hip", "encoder.cpp"]
+SOURCES = ["patdnn_api.hip", "kernel_fkw.hip", "kernel_tiled.hip", "copy_probe.hip", "selftest.hip", "encoder.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <string>
 
 #include "layout.hpp"
 
@@ -68,6 +69,9 @@ struct TiledVariant {
     hipError_t (*launch)(const DevTiled&, const ConvShape&, const float*, const float*, float*,
                          int32_t waves, int32_t ksplit, hipStream_t);
 };
+
+// Device check that s_movrels_b32 / _b64 behave as the threaded interpreter assumes.
+bool movrel_selftest(std::string& err);
 
 int num_tiled_variants();
 const TiledVariant& tiled_variant(int i);

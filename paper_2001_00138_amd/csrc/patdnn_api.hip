@@ -143,6 +143,10 @@ patdnn_status_t ensure_tiled(patdnn_layer* h, int vi, int ck, const DevTiled** o
     const std::pair<int, int> key(vi, ck);
     auto it = h->tiled.find(key);
     if (it == h->tiled.end()) {
+        if (v.threaded && h->on_device) {
+            std::string why;
+            if (!movrel_selftest(why)) return fail(PATDNN_EUNSUPPORTED, "threaded variants are off: " + why);
+        }
         std::unique_ptr<TiledOnDevice> t(new (std::nothrow) TiledOnDevice());
         if (!t) return fail(PATDNN_ENOMEM, "out of host memory");
         TiledParams prm;
@@ -608,6 +612,13 @@ patdnn_status_t patdnn_export_tiled(patdnn_handle_t h, int32_t variant, int32_t 
         (e = get(chunk_ptr, t->dev.chunk_ptr, t->host.chunk_ptr.data(), t->host.chunk_ptr.size() * 4)) != hipSuccess ||
         (e = get(steps, t->dev.steps, t->host.steps.data(), t->host.steps.size() * 4)) != hipSuccess)
         return hip_fail(e, "reading the tiled layout back");
+    return PATDNN_OK;
+}
+
+patdnn_status_t patdnn_selftest(void)
+{
+    std::string why;
+    if (!movrel_selftest(why)) return fail(PATDNN_EUNSUPPORTED, why);
     return PATDNN_OK;
 }
 
