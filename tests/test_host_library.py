@@ -309,3 +309,40 @@ def test_tiled_step_streams_decode_to_the_layer(oracle, config, layer, ck):
         assert sorted(c for c in t["slot_channel"].ravel() if c >= 0) == list(range(spec.c_out))
     assert seen >= 4          # call / threaded dispatch x one / two window register sets
     L.close()
+
+
+def test_step_streams_of_random_layers_decode_exactly():
+    """Random shapes, densities and chunk sizes (including filters without kernels, channels
+    nobody reads, group sizes that do not divide c_out, chunk sizes that do not divide
+    c_in): every sparse variant's stream rebuilds the layer bit for bit."""
+    from hypothesis import given, settings, strategies as st
+
+    lib = wl.pattern_library(wl.PATTERN_SEED)
+
+    @settings(max_examples=30, deadline=None, derandomize=True)
+    @given(c_out=st.integers(1, 70), c_in=st.integers(1, 40), keep=st.sampled_from([0.0, 0.1, 0.3, 0.6, 1.0]),
+           ck=st.integers(1, 19), stride=st.sampled_from([1, 2]), seed=st.integers(0, 10_000))
+    def run(c_out, c_in, keep, ck, stride, seed):
+        rng = np.random.default_rng(seed)
+        w = rng.standard_normal((c_out, c_in, 3, 3)).astype(np.float32)
+        ids = rng.integers(0, 8, (c_out, c_in), dtype=np.uint8)
+        mask = (rng.random((c_out, c_in)) < keep).astype(np.uint8)
+        L = B.Layer(w, ids, mask, lib, stride=stride, host_only=True)
+        bits = np.array([[(int(m) >> p) & 1 for p in range(9)] for m in lib], np.uint8).reshape(8, 3, 3)
+        want = np.where((mask[:, :, None, None] == 1) & (bits[ids] == 1), w, np.float32(0)).astype(np.float32)
+        try:
+            for v in range(1, B.patdnn_num_variants()):
+                try:
+                    t = L.export_tiled(v, ck)
+                except B.PatdnnError as e:
+                    assert e.status == B.PATDNN_EUNSUPPORTED
+                    continue
+                got_w, got_ids, km, walked = _walk_steps(t, lib, c_out, c_in)
+                assert got_w.view(np.uint32).tolist() == want.view(np.uint32).tolist()
+                np.testing.assert_array_equal(km, mask)
+                np.testing.assert_array_equal(got_ids[km == 1], ids[km == 1])
+                assert walked == t["num_steps"] - 1
+        finally:
+            L.close()
+
+    run()
