@@ -132,6 +132,22 @@ def test_ragged_shapes_and_modes(torch, oracle, case):
     _check_layer(torch, oracle, d, x, relu=False, use_bias=False, configs=[None])
 
 
+def test_all_56_patterns_on_every_slot(torch, oracle):
+    """The library may be any subset of the 56 centre-keeping patterns (section 4.1): every
+    (filter slot, pattern) code block of the tiled kernels runs here."""
+    uni = wl.pattern_universe()
+    c_out, c_in = 32, 56
+    rng = np.random.default_rng(5656)
+    spec = wl.LayerSpec(name="all_patterns", c_in=c_in, c_out=c_out, h=0, w=0)
+    d = {"spec": spec, "pattern_masks": uni,
+         "pattern_ids": ((np.arange(c_in)[None, :] + np.arange(c_out)[:, None]) % 56).astype(np.uint8),
+         "kernel_mask": np.ones((c_out, c_in), np.uint8),
+         "weights": rng.standard_normal((c_out, c_in, 3, 3)).astype(np.float32),
+         "bias": rng.standard_normal(c_out).astype(np.float32)}
+    x = rng.standard_normal((2, c_in, 14, 17)).astype(np.float32)
+    _check_layer(torch, oracle, d, x, configs=[None] + _all_configs())
+
+
 def test_degenerate_layers(torch, oracle):
     rng = np.random.default_rng(99)
     d = _random_layer(rng, 20, 12, 0.3)

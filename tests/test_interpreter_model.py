@@ -200,6 +200,23 @@ def test_model_runs_long_streams(oracle):
     assert len(seen) == 7
 
 
+def test_model_runs_every_block_of_the_table(oracle):
+    """All 56 centre-keeping patterns on every filter slot: each (slot, pattern) code block of
+    the table is executed at least once (section 4.1: the library may be any subset)."""
+    uni = wl.pattern_universe()
+    c_out, c_in = 16, 56
+    rng = np.random.default_rng(56)
+    d = {"pattern_masks": uni,
+         "pattern_ids": ((np.arange(c_in)[None, :] + np.arange(c_out)[:, None]) % 56).astype(np.uint8),
+         "kernel_mask": np.ones((c_out, c_in), np.uint8),
+         "weights": rng.standard_normal((c_out, c_in, 3, 3)).astype(np.float32),
+         "bias": rng.standard_normal(c_out).astype(np.float32)}
+    x = rng.standard_normal((1, c_in, 7, 9)).astype(np.float32)
+    seen = _check(oracle, d, x, 14, only={
+        "t_g16_p7x1_s1_x16", "t_g16_p7x1_s1_x16_thdw", "t_g8_p7x2_s1_x8_thw", "t_g12_p7x1_s1_x16_th"})
+    assert len(seen) == 4
+
+
 def test_model_catches_planted_mistakes(oracle):
     """The model has teeth: a wait taken out of the program, or a corrupted code offset
     in the stream, fails instead of passing by luck."""
