@@ -223,7 +223,7 @@ void build_tiled(const LayerHost& L, const TiledParams& prm, Tiled& T)
         for (int s = 0; s < c_out; ++s)
             for (int32_t k = f.offset[s]; k < f.offset[s + 1]; ++k) ++fc[(size_t)s * nc + f.index[k] / prm.ck];
         std::vector<int64_t> load((size_t)ng * nc, 0);
-        std::vector<int32_t> fill(ng, 0), group_of(c_out, 0);
+        std::vector<int32_t> fill(ng, 0);
         auto delta_sq = [&](int g, const int32_t* add, const int32_t* sub) {
             int64_t d = 0;                                           // change of sum(load^2) of group g
             for (int c = 0; c < nc; ++c) {
@@ -242,7 +242,6 @@ void build_tiled(const LayerHost& L, const TiledParams& prm, Tiled& T)
                 if (best < 0 || d < best_d) { best = g; best_d = d; }
             }
             members[(size_t)best * G + fill[best]++] = s;
-            group_of[s] = best;
             for (int c = 0; c < nc; ++c) load[(size_t)best * nc + c] += fc[(size_t)s * nc + c];
         }
         // bounded improvement by swaps; a fixed linear congruential sequence picks the pairs
