@@ -520,19 +520,38 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
     float best = -1.0f;
     patdnn_config_t best_cfg = cands.back();
     patdnn_status_t result = PATDNN_OK;
-    for (const auto& c : cands) {
-        const int reps = 3;
-        st = run_config(h, c, s, input, bias, output, stream);           // warm-up
-        if (st != PATDNN_OK) { result = st; break; }
+    // milliseconds per run of one candidate: one warm-up, then `reps` runs between two events
+    auto time_config = [&](const patdnn_config_t& c, int reps, float& ms) -> patdnn_status_t {
+        patdnn_status_t r = run_config(h, c, s, input, bias, output, stream);
+        if (r != PATDNN_OK) return r;
         (void)hipEventRecord(e0, stream);
-        for (int r = 0; r < reps && st == PATDNN_OK; ++r) st = run_config(h, c, s, input, bias, output, stream);
+        for (int k = 0; k < reps && r == PATDNN_OK; ++k) r = run_config(h, c, s, input, bias, output, stream);
         (void)hipEventRecord(e1, stream);
-        if (st != PATDNN_OK) { result = st; break; }
-        if ((e = hipEventSynchronize(e1)) != hipSuccess) { result = hip_fail(e, "hipEventSynchronize"); break; }
-        float ms = 0.0f;
+        if (r != PATDNN_OK) return r;
+        hipError_t he = hipEventSynchronize(e1);
+        if (he != hipSuccess) return hip_fail(he, "hipEventSynchronize");
+        ms = 0.0f;
         (void)hipEventElapsedTime(&ms, e0, e1);
-        ms /= reps;
-        if (best < 0.0f || ms < best) { best = ms; best_cfg = c; }
+        ms /= (float)reps;
+        return PATDNN_OK;
+    };
+    // first pass over every candidate, then the four fastest again with more runs: the
+    // winner of a noisy first pass should not stay by luck
+    std::vector<std::pair<float, size_t>> timed;
+    for (size_t i = 0; i < cands.size(); ++i) {
+        float ms = 0.0f;
+        st = time_config(cands[i], 3, ms);
+        if (st != PATDNN_OK) { result = st; break; }
+        timed.emplace_back(ms, i);
+    }
+    if (result == PATDNN_OK) {
+        std::sort(timed.begin(), timed.end());
+        for (size_t k = 0; k < timed.size() && k < 4; ++k) {
+            float ms = 0.0f;
+            st = time_config(cands[timed[k].second], 8, ms);
+            if (st != PATDNN_OK) { result = st; break; }
+            if (best < 0.0f || ms < best) { best = ms; best_cfg = cands[timed[k].second]; }
+        }
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
