@@ -154,12 +154,22 @@ def _win(g, ws, i):
 
 
 def _window_reads(asm, g, ws):
-    if g["wide"]:
+    if g["wide"] and g["WC"] % 2 == 0:
         # rows start 8-byte aligned in LDS (even patch width, even pitch): two floats per read
         for q in range(g["WR"]):
             for r in range(0, g["WC"], 2):
                 v = WIDE_WINDOW_BASE + ws * g["nwin"] + q * g["WC"] + r
                 asm(f"ds_read_b64 v[{v}:{v + 1}], %[addr] offset:{4 * (q * g['pitch'] + r)}")
+        return
+    if g["wide"]:
+        # odd window width: any two window elements per read (ds_read2_b32 takes two dword
+        # offsets below 256, which the band-major layout keeps them under)
+        base = WIDE_WINDOW_BASE + ws * g["nwin"]
+        offs = [q * g["pitch"] + r for q in range(g["WR"]) for r in range(g["WC"])]
+        for i in range(0, g["nwin"] - 1, 2):
+            asm(f"ds_read2_b32 v[{base + i}:{base + i + 1}], %[addr] offset0:{offs[i]} offset1:{offs[i + 1]}")
+        if g["nwin"] % 2:
+            asm(f"ds_read_b32 v{base + g['nwin'] - 1}, %[addr] offset:{4 * offs[-1]}")
         return
     for i in range(g["nwin"]):
         q, r = divmod(i, g["WC"])
@@ -348,8 +358,12 @@ def program(G, PR, PC, S, TGX, MODE):
     staged chunk, %[sp] the 64-bit address of the first step, %[entry] (threaded) the
     code offset of the first step transition."""
     g = geometry(G, PR, PC, S, TGX, MODE)
-    if g["wide"] and (g["WC"] % 2 or (PC * S) % 2 or g["nwin"] % 2):
-        raise ValueError("wide window reads need an even window width and an even lane step")
+    if g["wide"] and g["WC"] % 2 == 0 and ((PC * S) % 2 or g["pitch"] % 2):
+        raise ValueError("64-bit window reads need an even lane step and an even row pitch")
+    if g["wide"] and g["WC"] % 2 and (g["WR"] - 1) * g["pitch"] + g["WC"] > 255:
+        raise ValueError("paired window reads need every window offset below 256 dwords (band-major layout)")
+    if g["wide"] and g["sets"] * g["nwin"] % 2 and g["sets"] > 1:
+        raise ValueError("two fixed window sets need an even window size")
     build = _program_threaded if g["threaded"] else _program_call
     return build(G, PR, PC, S, TGX, MODE, g), g
 

@@ -67,7 +67,12 @@ class Program:
             if mo:
                 offset = int(mo.group(1), 0)
                 rest = rest[:mo.start()]
+            pair = re.search(r"\s+(offset0:\d+\s+offset1:\d+)$", rest)
+            if pair:
+                rest = rest[:pair.start()]
             args = [a.strip() for a in rest.split(",")] if rest else []
+            if pair:
+                args.append(pair.group(1))
             size = 4
             if op.startswith(("s_load", "ds_")):
                 size = 8
@@ -219,6 +224,23 @@ class Wave:
                     if f"v{int(lo) + k}" in self.pending_v:
                         raise ModelError("two LDS reads in flight into one register")
                     self.pending_v[f"v{int(lo) + k}"] = self.lds[va // 4 + k].copy()
+            elif op == "ds_read2_b32":
+                m2 = re.match(r"^offset0:(\d+)\s+offset1:(\d+)$", a[2]) if len(a) > 2 else None
+                if not m2:
+                    raise ModelError(f"ds_read2_b32 operands not understood: {a}")
+                lo, hi = re.match(r"^v\[(\d+):(\d+)\]$", a[0]).groups()
+                if int(hi) != int(lo) + 1:
+                    raise ModelError(f"bad destination {a[0]}")
+                for k in range(2):
+                    o = int(m2.group(1 + k))
+                    if o > 255:
+                        raise ModelError("ds_read2_b32 offset above 255 dwords")
+                    va = self.vreg(a[1]).astype(np.int64) + 4 * o
+                    if (va % 4).any() or (va < 0).any() or (va + 4 > self.lds.size * 4).any():
+                        raise ModelError(f"LDS read out of the staged region at {addr - p.base:#x}")
+                    if f"v{int(lo) + k}" in self.pending_v:
+                        raise ModelError("two LDS reads in flight into one register")
+                    self.pending_v[f"v{int(lo) + k}"] = self.lds[va // 4].copy()
             elif op == "v_add_u32":
                 src0 = a[1]
                 x0 = self.vreg(src0) if self.vkey(src0) in self.v else \
