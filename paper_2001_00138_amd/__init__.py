@@ -1,6 +1,6 @@
 """MI355X-native pattern-sparse 3x3 convolution (PatDNN inference hot path).
 
-The package holds three things and nothing else:
+The package holds:
 
 * ``workloads``  - seeded synthetic layer generators (shapes of the paper's
   VGG-16 / ResNet-50 / MobileNet-V2 workloads, section 6.1).  Pure data, none
@@ -9,9 +9,11 @@ The package holds three things and nothing else:
   (declared in ``include/patdnn.h``).  Every step of the path runs in the HIP
   library; there is no CPU fallback.
 * ``buildlib``   - compiles ``csrc/`` for gfx950 with hipcc.
+* ``tune_report``, ``profile_summary`` - command-line measurement tools (the
+  autotuner's search space as a table; rocprofv3 CSVs as short summaries).
 
 Importing the package does not load the shared library; ``binding`` does so on
 first use and raises if it is missing.
 """
 
-__all__ = ["workloads", "binding", "buildlib"]
+__all__ = ["workloads", "binding", "buildlib", "tune_report", "profile_summary"]
