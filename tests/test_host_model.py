@@ -153,3 +153,26 @@ def test_host_model_catches_planted_mistakes(tmp_path, oracle, plant):
     broken = _build_hostmodel(tmp_path, edits[plant])
     with pytest.raises(AssertionError):
         test_every_sparse_variant_on_the_host_model(broken, oracle, CASES[0])
+
+
+@pytest.mark.parametrize("ck,waves", [(6, 3), (9, 6), (12, 3), (24, 6), (1, 1), (40, 8)])
+def test_default_variant_over_the_tuner_grid(hostmodel, oracle, ck, waves):
+    """The launch parameters the tuner tries beyond the ones the GPU tests name: chunk sizes
+    that do not divide c_in, three and six wavefronts, more wavefronts than filter groups."""
+    rng = np.random.default_rng(77)
+    lib = wl.pattern_library(wl.PATTERN_SEED)
+    c_out, c_in = 64, 40
+    ids = rng.integers(0, 8, (c_out, c_in), dtype=np.uint8)
+    mask = (rng.random((c_out, c_in)) < 0.28).astype(np.uint8)
+    w = rng.standard_normal((c_out, c_in, 3, 3)).astype(np.float32)
+    bias = rng.standard_normal(c_out).astype(np.float32)
+    x = rng.standard_normal((2, c_in, 21, 30)).astype(np.float32)
+    ref = oracle.conv2d(w, ids, mask, lib, x, bias, stride=1, pad=1, relu=True)
+    L = B.Layer(w, ids, mask, lib, host_only=True)
+    for v in (1, 2):                                   # the two variants the tuner may choose today
+        t = L.export_tiled(v, ck)
+        min_waves = -(-hostmodel.hostmodel_variant_lds_floats(v - 1) // (64 * 7))
+        got = _run(hostmodel, v, t, x, bias, 1, 1, True, max(waves, min_waves), c_out)
+        assert not np.isnan(got).any()
+        assert float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max()) <= TOL
+    L.close()
