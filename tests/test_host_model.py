@@ -155,7 +155,7 @@ def test_host_model_catches_planted_mistakes(tmp_path, oracle, plant):
         test_every_sparse_variant_on_the_host_model(broken, oracle, CASES[0])
 
 
-@pytest.mark.parametrize("ck,waves", [(6, 3), (9, 6), (12, 3), (24, 6), (1, 1), (40, 8)])
+@pytest.mark.parametrize("ck,waves", [(6, 3), (9, 6), (12, 3), (24, 6), (1, 2), (28, 8)])
 def test_default_variant_over_the_tuner_grid(hostmodel, oracle, ck, waves):
     """The launch parameters the tuner tries beyond the ones the GPU tests name: chunk sizes
     that do not divide c_in, three and six wavefronts, more wavefronts than filter groups."""
