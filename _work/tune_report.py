@@ -15,7 +15,9 @@ from __future__ import annotations
 
 import argparse
 import json
+import os
 import sys
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 
 
 def _ints(text):
@@ -28,6 +30,7 @@ def main(argv=None) -> int:
     ap.add_argument("--layer", type=int, default=3)
     ap.add_argument("--batch", type=int, default=None)
     ap.add_argument("--variants", type=_ints, default=None, help="variant numbers (default: all that fit)")
+    ap.add_argument("--names", default=None, help="regex over variant names")
     ap.add_argument("--ck", type=_ints, default=[4, 8, 16])
     ap.add_argument("--waves", type=_ints, default=[2, 4, 8])
     ap.add_argument("--ksplit", type=_ints, default=[1], help="input-channel slices (>1 needs PATDNN_EXPERIMENTAL=1)")
@@ -36,8 +39,8 @@ def main(argv=None) -> int:
     args = ap.parse_args(argv)
 
     import torch
-    from . import binding as B
-    from . import workloads as wl
+    from paper_2001_00138_amd import binding as B
+    from paper_2001_00138_amd import workloads as wl
 
     if not torch.cuda.is_available():
         print("tune_report: no GPU visible", file=sys.stderr)
@@ -55,6 +58,9 @@ def main(argv=None) -> int:
     nz = wl.nz_flops(spec, kept)
     rows = []
     variants = args.variants if args.variants is not None else list(range(B.patdnn_num_variants()))
+    if args.names:
+        import re
+        variants = [v for v in variants if re.search(args.names, B.patdnn_variant_name(v))]
     for v in variants:
         name = B.patdnn_variant_name(v)
         combos = [(0, 0, 1)] if v == B.PATDNN_VARIANT_FKW else \

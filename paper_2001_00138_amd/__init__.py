@@ -9,11 +9,11 @@ The package holds:
   (declared in ``include/patdnn.h``).  Every step of the path runs in the HIP
   library; there is no CPU fallback.
 * ``buildlib``   - compiles ``csrc/`` for gfx950 with hipcc.
-* ``tune_report``, ``profile_summary`` - command-line measurement tools (the
-  autotuner's search space as a table; rocprofv3 CSVs as short summaries).
+* ``profile_summary`` - turns rocprofv3 CSVs into the short summaries kept in
+  ``profiles/``.
 
 Importing the package does not load the shared library; ``binding`` does so on
 first use and raises if it is missing.
 """
 
-__all__ = ["workloads", "binding", "buildlib", "tune_report", "profile_summary"]
+__all__ = ["workloads", "binding", "buildlib", "profile_summary"]

@@ -27,6 +27,7 @@
 //   * Dense (unpruned) layers use the same staging and register tiling with a plain
 //     9-tap loop and no stream.
 #include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 #include "kernels.hpp"
@@ -44,7 +45,18 @@ struct TiledArgs {
     const float* w9;
     int32_t n, c_in, c_out, h, w, ho, wo, pad, relu;
     int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets;
+#ifdef PATDNN_TIMELINE
+    unsigned long long* tl;      // [blocks][8 waves][8 phases] cycle totals (debug builds only)
+#endif
 };
+
+#ifdef PATDNN_TIMELINE
+#define TL_DECL unsigned long long tl_t = __builtin_readcyclecounter(), tl_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}
+#define TL_MARK(k) do { const unsigned long long now = __builtin_readcyclecounter(); tl_acc[k] += now - tl_t; tl_t = now; } while (0)
+#else
+#define TL_DECL
+#define TL_MARK(k)
+#endif
 
 template <int G_, int PR_, int PC_, int S_, int TGX_, bool DENSE_, int MAXSLOTS_, int MODE_>
 struct Geo {
@@ -107,6 +119,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     constexpr int G = GEO::G, PR = GEO::PR, PC = GEO::PC, S = GEO::S, TGX = GEO::TGX;
     constexpr int NB = GEO::NB, WR = GEO::WR, WC = GEO::WC, PITCH = GEO::PITCH;
     extern __shared__ float lds[];
+    TL_DECL;
 
     const int tid = threadIdx.x;
     const int nthreads = blockDim.x;
@@ -166,21 +179,39 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     lds_f32* const lds3 = (lds_f32*)lds;
     const int buf_floats = a.ck * GEO::TILEP;
 
-    auto stage = [&](int c0, lds_f32* buf) {
+    // Staging instructions of this wavefront per channel: slot k fills LDS dwords
+    // [wave*64 + k*nthreads, +64) of the channel, so the count is the same for every channel
+    // and the per-channel code is straight-line (a taken branch costs about as much as ten
+    // loads take to issue).
+    const int my_slots = __builtin_amdgcn_readfirstlane(
+        max(0, min((int)GEO::MAXSLOTS, (GEO::TILEP - wave * 64 + nthreads - 1) / nthreads)));
+    auto stage_n = [&](auto nk_tag, int c0, lds_f32* buf) __attribute__((always_inline)) {
+        constexpr int NK = decltype(nk_tag)::value;
         const int cn = min(a.ck, a.c_in - c0);
+        const char* src = (const char*)in_blk + (size_t)c0 * plane * 4;
+        size_t left = blk_bytes - (size_t)c0 * plane * 4;
+        lds_f32* dst = buf + wave * 64;
         for (int c = 0; c < cn; ++c) {
-            const size_t off = (size_t)(c0 + c) * plane * 4;
-            const size_t left = blk_bytes - off;
             const unsigned nrec = left > 0xFFFFFFFFull ? 0xFFFFFFFFu : (unsigned)left;
-            __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-                (void*)((const char*)in_blk + off), 0, (int)nrec, 0x00020000);
+            __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)src, 0, (int)nrec, 0x00020000);
 #pragma unroll
-            for (int k = 0; k < GEO::MAXSLOTS; ++k) {
-                const int eb = wave * 64 + k * nthreads;          // wave-uniform
-                if (eb < GEO::TILEP)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, buf + c * GEO::TILEP + eb, 4,
-                                                             (int)voff[k], 0, 0, 0);
-            }
+            for (int k = 0; k < NK; ++k)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, dst + k * nthreads, 4, (int)voff[k], 0, 0, 0);
+            src += (size_t)plane * 4;
+            left -= (size_t)plane * 4;
+            dst += GEO::TILEP;
+        }
+    };
+    auto stage = [&](int c0, lds_f32* buf) __attribute__((always_inline)) {
+        static_assert(GEO::MAXSLOTS <= 16, "staging slots per thread");
+        switch (my_slots) {
+#define PATDNN_STAGE_CASE(n) case n: if constexpr (n <= GEO::MAXSLOTS) stage_n(std::integral_constant<int, n>{}, c0, buf); break;
+            PATDNN_STAGE_CASE(1) PATDNN_STAGE_CASE(2) PATDNN_STAGE_CASE(3) PATDNN_STAGE_CASE(4)
+            PATDNN_STAGE_CASE(5) PATDNN_STAGE_CASE(6) PATDNN_STAGE_CASE(7) PATDNN_STAGE_CASE(8)
+            PATDNN_STAGE_CASE(9) PATDNN_STAGE_CASE(10) PATDNN_STAGE_CASE(11) PATDNN_STAGE_CASE(12)
+            PATDNN_STAGE_CASE(13) PATDNN_STAGE_CASE(14) PATDNN_STAGE_CASE(15) PATDNN_STAGE_CASE(16)
+#undef PATDNN_STAGE_CASE
+            default: break;
         }
     };
 
@@ -219,7 +250,9 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     // workgroups per CU); the chunk is loaded after everyone has left the previous one and
     // the other workgroups of the CU cover the wait.  Otherwise two alternating buffers.
     constexpr bool ONE_BUFFER = (GEO::MODE & 16) != 0;
+    TL_MARK(0);                                   // prologue
     if constexpr (!ONE_BUFFER) stage(c_first, lds3);
+    TL_MARK(2);
     for (int c0 = c_first, chunk = SPLITK ? chunk_first : 0; c0 < c_end; c0 += a.ck, ++chunk) {
         const int cn = min(a.ck, a.c_in - c0);
         const int cur = ONE_BUFFER ? 0 : ((SPLITK ? chunk - chunk_first : chunk) & 1) * buf_floats;
@@ -232,8 +265,11 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
             // chunk `chunk` has landed in this wavefront's view, and (barrier) in everyone's;
             // everyone has also finished reading the other buffer
             __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+            TL_MARK(1);                           // wait for the staged chunk
             __syncthreads();
+            TL_MARK(5);                           // barrier
             if (c0 + a.ck < c_end) stage(c0 + a.ck, lds3 + (buf_floats - cur));
+            TL_MARK(2);                           // issuing the next chunk's loads
         }
 
         if (group_ok) {
@@ -272,6 +308,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                           a.steps + (size_t)start * kStepDwords, (cp >> kChunkEntryShift) * Loop::kCtrlBytes);
             }
         }
+        TL_MARK(3);                               // the chunk's kernels
     }
 
     // ---- epilogue: bias, ReLU, scatter to the original output channel
@@ -298,7 +335,17 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                 }
         }
     }
+#ifdef PATDNN_TIMELINE
+    TL_MARK(4);                                   // epilogue (stores issued)
+    if (a.tl && lane == 0)
+        for (int k = 0; k < 8; ++k) a.tl[((size_t)blockIdx.x * 8 + wave) * 8 + k] = tl_acc[k];
+#endif
 }
+
+#ifdef PATDNN_TIMELINE
+static unsigned long long* g_timeline = nullptr;
+extern "C" void patdnn_debug_timeline(unsigned long long* p) { g_timeline = p; }
+#endif
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float* p, size_t n)
 {
@@ -317,6 +364,20 @@ __global__ __launch_bounds__(256) void bias_act_kernel(float* out, const float* 
         if (relu) v = fmaxf(v, 0.0f);
         out[i] = v;
     }
+}
+
+// More than 64 KB of dynamic LDS needs the function attribute, once per device (bit = device
+// id); two threads racing here both set it, which is harmless.
+static hipError_t allow_big_lds(const void* fn, std::atomic<uint64_t>& done)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
 }
 
 template <class GEO>
@@ -338,15 +399,16 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
     a.num_bands = (int32_t)bands;
     a.ck = t.ck; a.num_chunks = t.num_chunks; a.waves = waves;
     a.fgsets = (t.num_groups + waves - 1) / waves;
+#ifdef PATDNN_TIMELINE
+    a.tl = g_timeline;
+#endif
     const long long blocks = tiles * a.fgsets;
     if (bands > INT32_MAX || blocks > INT32_MAX) return hipErrorInvalidValue;
     const size_t lds_bytes = ((GEO::MODE & 16) ? 1 : 2) * (size_t)t.ck * GEO::TILEP * sizeof(float);   // staging buffers
-    static bool big_lds_allowed = false;
-    if (lds_bytes > 64 * 1024 && !big_lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, false>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (lds_bytes > 64 * 1024) {
+        static std::atomic<uint64_t> allowed{0};
+        hipError_t e = allow_big_lds(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, false>), allowed);
         if (e != hipSuccess) return e;
-        big_lds_allowed = true;
     }
     if (ksplit <= 1) {
         hipLaunchKernelGGL((tiled_conv_kernel<GEO, false>), dim3((unsigned)blocks), dim3(64 * waves), lds_bytes,
@@ -358,12 +420,10 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
         return hipErrorInvalidValue;
     } else {
         if (ksplit > t.num_chunks || ksplit > 65535) return hipErrorInvalidValue;
-        static bool big_lds_allowed_k = false;
-        if (lds_bytes > 64 * 1024 && !big_lds_allowed_k) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, true>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (lds_bytes > 64 * 1024) {
+            static std::atomic<uint64_t> allowed_k{0};
+            hipError_t e = allow_big_lds(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, true>), allowed_k);
             if (e != hipSuccess) return e;
-            big_lds_allowed_k = true;
         }
         const size_t plane = (size_t)s.ho * s.wo, total = (size_t)s.n * s.c_out * plane;
         const unsigned fill_blocks = (unsigned)std::min<size_t>((total + 255) / 256, 256 * 32);

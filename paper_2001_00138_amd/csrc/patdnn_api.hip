@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <iterator>
 #include <map>
 #include <memory>
 #include <new>
@@ -37,6 +38,11 @@ patdnn_status_t hip_fail(hipError_t e, const char* what)
 struct TiledOnDevice {
     Tiled host;
     DevTiled dev;
+    std::vector<void*> allocations;       // device arrays of this layout
+    ~TiledOnDevice()
+    {
+        for (void* p : allocations) (void)hipFree(p);
+    }
 };
 
 }  // namespace
@@ -50,6 +56,7 @@ struct patdnn_layer {
     std::map<std::pair<int, int>, std::unique_ptr<TiledOnDevice>> tiled;
     std::vector<void*> allocations;
     patdnn_config_t cfg{-1, 0, 0, 1};                      // variant -1: choose per call
+    bool cfg_tuned = false;                                // cfg came from patdnn_tune (for one input size)
 
     ~patdnn_layer()
     {
@@ -60,7 +67,7 @@ struct patdnn_layer {
 namespace {
 
 template <class T>
-hipError_t upload(patdnn_layer* h, const std::vector<T>& v, const T** out, size_t extra = 0)
+hipError_t upload(std::vector<void*>& owner, const std::vector<T>& v, const T** out, size_t extra = 0)
 {
     *out = nullptr;
     const size_t bytes = (v.size() + extra) * sizeof(T);
@@ -68,7 +75,7 @@ hipError_t upload(patdnn_layer* h, const std::vector<T>& v, const T** out, size_
     void* p = nullptr;
     hipError_t e = hipMalloc(&p, bytes);
     if (e != hipSuccess) return e;
-    h->allocations.push_back(p);
+    owner.push_back(p);
     if (extra) {
         e = hipMemset(p, 0, bytes);
         if (e != hipSuccess) return e;
@@ -167,10 +174,10 @@ patdnn_status_t ensure_tiled(patdnn_layer* h, int vi, int ck, const DevTiled** o
         t->dev.num_chunks = t->host.num_chunks;
         if (h->on_device) {
             hipError_t e;
-            if ((e = upload(h, t->host.slot_channel, &t->dev.slot_channel)) != hipSuccess ||
-                (e = upload(h, t->host.chunk_ptr, &t->dev.chunk_ptr)) != hipSuccess ||
-                (e = upload(h, t->host.steps, &t->dev.steps)) != hipSuccess ||
-                (e = upload(h, t->host.w9, &t->dev.w9)) != hipSuccess)
+            if ((e = upload(t->allocations, t->host.slot_channel, &t->dev.slot_channel)) != hipSuccess ||
+                (e = upload(t->allocations, t->host.chunk_ptr, &t->dev.chunk_ptr)) != hipSuccess ||
+                (e = upload(t->allocations, t->host.steps, &t->dev.steps)) != hipSuccess ||
+                (e = upload(t->allocations, t->host.w9, &t->dev.w9)) != hipSuccess)
                 return hip_fail(e, "uploading the tiled layout");
         }
         it = h->tiled.emplace(key, std::move(t)).first;
@@ -208,8 +215,8 @@ patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const Conv
     if (vi < 0 || vi >= num_tiled_variants()) return fail(PATDNN_EINVAL, "no such variant");
     const TiledVariant& v = tiled_variant(vi);
     if (!variant_fits_layer(h, v)) return fail(PATDNN_EUNSUPPORTED, "variant cannot run this layer");
-    if ((v.experimental || c.ksplit > 1) && !experimental_allowed())
-        return fail(PATDNN_EUNSUPPORTED, "experimental variant / ksplit: set PATDNN_EXPERIMENTAL=1 to run it");
+    if (v.experimental && !experimental_allowed())
+        return fail(PATDNN_EUNSUPPORTED, "experimental variant: set PATDNN_EXPERIMENTAL=1 to run it");
     if (c.ksplit > 1 && v.dense) return fail(PATDNN_EUNSUPPORTED, "ksplit is for sparse variants");
     int32_t ck = c.ck, waves = c.waves;
     if (!resolve_tiled_params(h, v, s, ck, waves))
@@ -264,23 +271,25 @@ patdnn_status_t patdnn_encode(const patdnn_layer_desc_t* desc, const float* dens
         hipError_t e = hipGetDevice(&h->device);
         if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
         const Fkw& f = h->L.fkw;
-        if ((e = upload(h.get(), f.offset, &h->dfkw.offset)) != hipSuccess ||
-            (e = upload(h.get(), f.reorder, &h->dfkw.reorder)) != hipSuccess ||
-            (e = upload(h.get(), f.index, &h->dfkw.index)) != hipSuccess ||
-            (e = upload(h.get(), f.stride, &h->dfkw.stride)) != hipSuccess ||
-            (e = upload(h.get(), f.weight, &h->dfkw.weight)) != hipSuccess ||
-            (e = upload(h.get(), f.masks, &h->dfkw.masks)) != hipSuccess)
+        if ((e = upload(h->allocations, f.offset, &h->dfkw.offset)) != hipSuccess ||
+            (e = upload(h->allocations, f.reorder, &h->dfkw.reorder)) != hipSuccess ||
+            (e = upload(h->allocations, f.index, &h->dfkw.index)) != hipSuccess ||
+            (e = upload(h->allocations, f.stride, &h->dfkw.stride)) != hipSuccess ||
+            (e = upload(h->allocations, f.weight, &h->dfkw.weight)) != hipSuccess ||
+            (e = upload(h->allocations, f.masks, &h->dfkw.masks)) != hipSuccess)
             return hip_fail(e, "uploading the FKW arrays");
         h->dfkw.num_patterns = f.num_patterns;
         h->dfkw.taps = f.taps;
         h->on_device = true;
     }
-    // build (and upload) the group layouts of every tiled variant that can run the layer
+    // build (and upload) the group layout of the default variant; the layouts of the other
+    // variants are built when patdnn_set_config or patdnn_tune asks for them
     try {
         for (int vi = 0; vi < num_tiled_variants(); ++vi)
             if (variant_selectable(h.get(), tiled_variant(vi))) {
                 st = ensure_tiled(h.get(), vi, default_ck(tiled_variant(vi), desc->c_in), nullptr);
                 if (st != PATDNN_OK) return st;
+                break;
             }
     } catch (const std::bad_alloc&) {
         return fail(PATDNN_ENOMEM, "out of host memory");
@@ -321,8 +330,9 @@ patdnn_status_t patdnn_conv2d(patdnn_handle_t h, const float* input, int32_t n, 
     patdnn_config_t c = h->cfg;
     if (c.variant < 0) c = default_config(h, s);
     st = run_config(h, c, s, input, bias, output, static_cast<hipStream_t>(stream));
-    if (st == PATDNN_EUNSUPPORTED && h->cfg.variant > 0) {
-        // a configuration chosen for another input size may not fit this one
+    if (st == PATDNN_EUNSUPPORTED && h->cfg.variant > 0 && h->cfg_tuned) {
+        // a configuration tuned for another input size may not fit this one; a configuration
+        // the caller set explicitly is never replaced: the error goes back instead
         c = default_config(h, s);
         st = run_config(h, c, s, input, bias, output, static_cast<hipStream_t>(stream));
     }
@@ -433,6 +443,7 @@ patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
     if (!h || !cfg) return fail(PATDNN_EINVAL, "handle / cfg is NULL");
     if (cfg->variant < 0) {               // back to automatic choice
         h->cfg = patdnn_config_t{-1, 0, 0, 1};
+        h->cfg_tuned = false;
         return PATDNN_OK;
     }
     if (cfg->variant > num_tiled_variants()) return fail(PATDNN_EINVAL, "no such variant");
@@ -443,27 +454,32 @@ patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
             return fail(PATDNN_EUNSUPPORTED, "experimental variant: set PATDNN_EXPERIMENTAL=1 to run it");
         if (cfg->ck < 0 || cfg->waves < 0 || cfg->waves > kMaxWaves || cfg->ksplit < 0 || cfg->ksplit > 64)
             return fail(PATDNN_EINVAL, "ck / waves / ksplit out of range");
-        if (cfg->ksplit > 1 && (v.dense || (h->on_device && !experimental_allowed())))
-            return fail(PATDNN_EUNSUPPORTED, "ksplit: sparse variants only, and PATDNN_EXPERIMENTAL=1");
+        if (cfg->ksplit > 1 && v.dense) return fail(PATDNN_EUNSUPPORTED, "ksplit: sparse variants only");
         const int min_waves = (v.stage_elems + 64 * v.max_slots - 1) / (64 * v.max_slots);
         if (cfg->waves && cfg->waves < min_waves)
             return fail(PATDNN_EUNSUPPORTED, "too few wavefronts to stage a tile");
         if (cfg->ck && cfg->ck * 4 * v.lds_buffers * v.lds_floats_per_channel > kMaxLdsBytes)
             return fail(PATDNN_EUNSUPPORTED, "ck exceeds the LDS budget");
     }
-    h->cfg = *cfg;
-    if (h->cfg.ksplit < 1 || cfg->variant <= 0) h->cfg.ksplit = 1;
-    if (cfg->variant > 0) {
-        const TiledVariant& v = tiled_variant(cfg->variant - 1);
-        if (h->cfg.ck == 0) h->cfg.ck = default_ck(v, h->L.desc.c_in);
-        h->cfg.ck = std::min(h->cfg.ck, h->L.desc.c_in);
+    patdnn_config_t c = *cfg;
+    if (c.ksplit < 1 || c.variant <= 0) c.ksplit = 1;
+    if (c.variant > 0) {
+        const TiledVariant& v = tiled_variant(c.variant - 1);
+        if (c.ck == 0) c.ck = default_ck(v, h->L.desc.c_in);
+        c.ck = std::min(c.ck, h->L.desc.c_in);
         try {
-            patdnn_status_t st = ensure_tiled(h, cfg->variant - 1, h->cfg.ck, nullptr);
+            patdnn_status_t st = ensure_tiled(h, c.variant - 1, c.ck, nullptr);
             if (st != PATDNN_OK) return st;
         } catch (const std::bad_alloc&) {
             return fail(PATDNN_ENOMEM, "out of host memory");
         }
+        // an explicit configuration is taken as given or refused, never replaced at launch time
+        const int num_chunks = v.dense ? (h->L.desc.c_in + c.ck - 1) / c.ck
+                                       : h->tiled.find(std::make_pair(c.variant - 1, c.ck))->second->host.num_chunks;
+        if (c.ksplit > num_chunks) return fail(PATDNN_EUNSUPPORTED, "ksplit exceeds the number of channel chunks");
     }
+    h->cfg = c;
+    h->cfg_tuned = false;
     return PATDNN_OK;
 }
 
@@ -486,28 +502,33 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
     hipStream_t stream = static_cast<hipStream_t>(stream_);
 
     std::vector<patdnn_config_t> cands;
-    // 9 and 12 are the largest chunk sizes that still fit three / two workgroups of the
-    // 7x1 tiles into one CU's LDS; 3 and 6 wavefronts give workgroup counts in between
-    const int ck_opts[] = {4, 6, 8, 9, 12, 16, 24, 32};
-    const int wave_opts[] = {1, 2, 3, 4, 6, 8};
+    // The grid: chunk sizes 8 and 16 (smaller ones lose to their barrier count, larger ones to
+    // LDS occupancy on every layer measured), 4 or 8 wavefronts per workgroup (fewer only when
+    // the layer has fewer filter groups), and input-channel slices only for launches that
+    // cannot fill the chip's wavefront slots three times over.
+    const int ck_opts[] = {8, 16};
+    const int wave_opts[] = {1, 2, 4, 8};
+    const long long kWaveSlots = 256 * 4 * 3;
     for (int vi = 0; vi < num_tiled_variants(); ++vi) {
         const TiledVariant& v = tiled_variant(vi);
         if (!(variant_selectable(h, v) || (experimental_allowed() && variant_fits_layer(h, v)))) continue;
         const int groups = (s.c_out + v.G - 1) / v.G;
+        const long long bands = (long long)s.n * ((s.wo + v.TGX * v.PC - 1) / (v.TGX * v.PC)) * ((s.ho + v.PR - 1) / v.PR);
+        const long long wavefronts = (bands + 64 / v.TGX - 1) / (64 / v.TGX) * groups;
         for (int ck : ck_opts)
             for (int waves : wave_opts) {
                 int32_t ck2 = std::min(ck, s.c_in), w2 = waves;
+                if (w2 < 4 && groups >= 4) continue;           // small workgroups only for few groups
                 if (w2 > 1 && w2 / 2 >= groups) continue;      // mostly idle wavefronts
                 if (!resolve_tiled_params(h, v, s, ck2, w2)) continue;
-                if (ensure_tiled(h, vi, ck2, nullptr) != PATDNN_OK) continue;
-                // input-channel slices only when experimental code paths are allowed
                 const int num_chunks = (s.c_in + ck2 - 1) / ck2;
-                for (int ks = 1; ks <= (experimental_allowed() && !v.dense ? 4 : 1) && ks <= num_chunks; ++ks) {
+                for (int ks : {1, 2, 4}) {
+                    if (ks > 1 && (v.dense || ks > num_chunks || wavefronts * (ks / 2) >= 3 * kWaveSlots)) continue;
                     patdnn_config_t c{vi + 1, ck2, w2, ks};
                     bool dup = false;
                     for (const auto& o : cands)
                         dup |= (o.variant == c.variant && o.ck == c.ck && o.waves == c.waves && o.ksplit == c.ksplit);
-                    if (!dup) cands.push_back(c);
+                    if (!dup && ensure_tiled(h, vi, ck2, nullptr) == PATDNN_OK) cands.push_back(c);
                 }
             }
     }
@@ -561,6 +582,18 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
     if (st != PATDNN_OK) return st;
     if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
     h->cfg = best_cfg;
+    h->cfg_tuned = true;
+    // keep the winner's layout and the default variant's; free the others
+    {
+        const patdnn_config_t dflt = default_config(h, s);
+        for (auto it = h->tiled.begin(); it != h->tiled.end();) {
+            const int vnum = it->first.first + 1;
+            const bool dense = tiled_variant(it->first.first).dense;
+            const bool keep = (vnum == best_cfg.variant && (dense || it->first.second == best_cfg.ck)) ||
+                              (vnum == dflt.variant && (dense || it->first.second == dflt.ck));
+            it = keep ? std::next(it) : h->tiled.erase(it);
+        }
+    }
     if (best_us) *best_us = best * 1000.0f;
     return PATDNN_OK;
 }

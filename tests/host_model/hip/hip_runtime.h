@@ -39,6 +39,7 @@ constexpr hipError_t hipSuccess = 0, hipErrorInvalidValue = 1;
 constexpr int hipFuncAttributeMaxDynamicSharedMemorySize = 8;
 inline hipError_t hipGetLastError() { return hipSuccess; }
 inline hipError_t hipFuncSetAttribute(const void*, int, int) { return hipSuccess; }
+inline hipError_t hipGetDevice(int* d) { *d = 0; return hipSuccess; }
 
 namespace hostmodel {
 
@@ -67,6 +68,7 @@ namespace patdnn { extern float lds[]; }
 
 inline void __syncthreads() { pthread_barrier_wait(&hostmodel::state().barrier); }
 inline int min(int a, int b) { return a < b ? a : b; }
+inline int max(int a, int b) { return a > b ? a : b; }
 
 // hardware fp32 atomic add: workgroups run one after another here and the lanes of a
 // workgroup add to distinct elements, so a locked add is enough

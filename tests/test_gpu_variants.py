@@ -1,10 +1,9 @@
-"""GPU parity of the variants and launch options that are still experimental (threaded
-dispatch, 7x2 patches, 7-lane bands, stride-2 tiles, input-channel slices).  They have
-passed the host models (tests/test_interpreter_model.py, tests/test_host_model.py) but
-not yet a hardware run, so the library only runs them with PATDNN_EXPERIMENTAL=1 in the
-environment; without it this module is skipped.  Same bar as the other parity tests."""
+"""GPU parity of every tiled variant (call and threaded dispatch, 7x2 patches, 7-lane
+bands, band-major LDS layout, single staging buffer, stride-2 tiles) and of the split over
+input channels (ksplit), on ragged layers, element by element against the oracle.  An
+explicitly set configuration is taken as given or refused, never replaced, so each row
+printed here is the variant that really ran.  Same bar as the other parity tests."""
 
-import os
 import sys
 
 import numpy as np
@@ -13,9 +12,7 @@ import pytest
 from paper_2001_00138_amd import binding as B
 from paper_2001_00138_amd import workloads as wl
 
-pytestmark = [pytest.mark.gpu,
-              pytest.mark.skipif(os.environ.get("PATDNN_EXPERIMENTAL") != "1",
-                                 reason="experimental variants run only with PATDNN_EXPERIMENTAL=1")]
+pytestmark = pytest.mark.gpu
 TOL = 1e-5
 
 
@@ -40,11 +37,14 @@ CASES = [
     dict(c_out=40, c_in=7, n=2, h=29, w=17, keep=0.5, ck=4, waves=8, pad=0),
     dict(c_out=32, c_in=16, n=2, h=21, w=20, keep=0.3, ck=8, waves=4, stride=2),
     dict(c_out=128, c_in=128, n=4, h=56, w=56, keep=0.278, ck=8, waves=4),
+    dict(c_out=64, c_in=32, n=2, h=30, w=27, keep=0.3, ck=8, waves=4, stride=2, pad=0),
+    dict(c_out=48, c_in=40, n=2, h=19, w=23, keep=0.3, ck=9, waves=3),       # the tuner's odd grid points
+    dict(c_out=96, c_in=48, n=1, h=14, w=14, keep=0.3, ck=24, waves=6),
 ]
 
 
 @pytest.mark.parametrize("case", CASES)
-def test_experimental_variants_match_the_oracle(torch, oracle, case):
+def test_every_variant_and_ksplit_matches_the_oracle(torch, oracle, case):
     rng = np.random.default_rng(9000 + case["c_out"] + case["h"])
     lib = wl.pattern_library(wl.PATTERN_SEED)
     stride, pad = case.get("stride", 1), case.get("pad", 1)
@@ -63,21 +63,15 @@ def test_experimental_variants_match_the_oracle(torch, oracle, case):
         for v in range(1, B.patdnn_num_variants()):
             for ksplit in (1, 2, 3):
                 try:
-                    info = B.patdnn_tiled_info(L.handle, v, case["ck"])
-                    if not info["experimental"] and ksplit == 1:
-                        continue                      # covered by test_gpu_parity.py
                     L.set_config(v, case["ck"], case["waves"], ksplit)
                 except B.PatdnnError as e:
-                    assert e.status == B.PATDNN_EUNSUPPORTED
+                    assert e.status == B.PATDNN_EUNSUPPORTED      # wrong stride, dense, ksplit > chunks
                     continue
+                assert L.get_config()["variant"] == v
                 _say(f"  {case} variant {B.patdnn_variant_name(v)} ksplit={ksplit}")
                 buf = torch.full((numel + 2 * guard,), 12345.0, dtype=torch.float32, device="cuda")
                 out = buf[guard:guard + numel].view(shape)
-                try:
-                    L.conv2d(xt, bt, out, relu=True)
-                except B.PatdnnError as e:
-                    assert e.status == B.PATDNN_EUNSUPPORTED    # e.g. ksplit beyond the chunk count
-                    continue
+                L.conv2d(xt, bt, out, relu=True)      # an accepted explicit configuration must run
                 torch.cuda.synchronize()
                 assert bool((buf[:guard] == 12345.0).all()) and bool((buf[guard + numel:] == 12345.0).all())
                 got = out.cpu().numpy()

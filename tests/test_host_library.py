@@ -374,3 +374,21 @@ def test_fkw_index_overhead_against_csr_matches_the_paper():
     total_saving = (csr_bytes - fkw_bytes) / (csr_bytes + weight_bytes)
     assert abs(index_saving - float(g["fkw_vs_csr_index_saving_8x"][0])) < 0.02
     assert abs(total_saving - float(g["fkw_vs_csr_total_saving_8x"][0])) < 0.01
+
+
+def test_an_explicit_configuration_is_strict():
+    """A configuration the caller sets is accepted or refused, never replaced by another:
+    more input-channel slices than the layer has chunks is an error at set_config time."""
+    rng = np.random.default_rng(3)
+    lib = wl.pattern_library(wl.PATTERN_SEED)
+    c_out, c_in = 16, 7
+    L = B.Layer(rng.standard_normal((c_out, c_in, 3, 3)).astype(np.float32),
+                rng.integers(0, 8, (c_out, c_in), dtype=np.uint8),
+                (rng.random((c_out, c_in)) < 0.5).astype(np.uint8), lib, host_only=True)
+    L.set_config(1, 4, 4, 2)                       # 7 channels in chunks of 4: two chunks
+    assert L.get_config() == {"variant": 1, "ck": 4, "waves": 4, "ksplit": 2}
+    with pytest.raises(B.PatdnnError) as e:
+        L.set_config(1, 4, 4, 3)
+    assert e.value.status == B.PATDNN_EUNSUPPORTED
+    assert L.get_config()["ksplit"] == 2           # the refused configuration replaced nothing
+    L.close()

@@ -169,7 +169,8 @@ def test_default_variant_over_the_tuner_grid(hostmodel, oracle, ck, waves):
     x = rng.standard_normal((2, c_in, 21, 30)).astype(np.float32)
     ref = oracle.conv2d(w, ids, mask, lib, x, bias, stride=1, pad=1, relu=True)
     L = B.Layer(w, ids, mask, lib, host_only=True)
-    for v in (1, 2):                                   # the two variants the tuner may choose today
+    names = {B.patdnn_variant_name(v): v for v in range(1, B.patdnn_num_variants())}
+    for v in (names["t_g16_p7x1_s1_x16"], names["t_g8_p7x2_s1_x8_thw1b"]):   # call and threaded dispatch
         t = L.export_tiled(v, ck)
         min_waves = -(-hostmodel.hostmodel_variant_lds_floats(v - 1) // (64 * 7))
         got = _run(hostmodel, v, t, x, bias, 1, 1, True, max(waves, min_waves), c_out)
