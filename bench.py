@@ -8,14 +8,20 @@ A "step" is one pass over all 13 layers.  Inputs, weights and outputs are reside
 in HBM before the timed region starts.
 
 Prints ONE JSON line.  `value` is effective GFLOP/s over non-zero FLOPs
-(2 x 4 x kept kernels x output pixels; 2 x 9 for the dense first layer).
+(2 x 4 x kept kernels x output pixels; 2 x 9 for the dense first layer).  Beside it:
+the roofline of the dominant kernel, per-layer rows of this stack and of the
+ResNet-50-shaped and MobileNet-V2-shaped (depthwise, HBM-bound) stacks, peaks measured
+in the same run (stream copy, plain FMA loop), batch-1 stack latencies, the dense
+comparison and the CPU oracle's rate.
 """
 
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
+import re
 import sys
 import time
 
@@ -25,6 +31,7 @@ if ROOT not in sys.path:
 
 PEAK_FP32_VECTOR_TFLOPS = 157.3      # published; counts packed FP32 FMAs (2 per lane per clock)
 PEAK_FP32_NONPACKED_TFLOPS = 78.6    # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz
+PEAK_HBM_GBPS = 8000.0               # published HBM3E bandwidth
 
 
 def _log(msg):
@@ -34,17 +41,31 @@ def _log(msg):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, help="workload configuration (5 = N=64 VGG stack)")
     ap.add_argument("--batch", type=int, default=None, help="override the batch size")
-    ap.add_argument("--no-tune", action="store_true")
+    ap.add_argument("--tune", action="store_true",
+                    help="run the autotuner on every layer, also on those the configuration file covers")
+    ap.add_argument("--no-tune", action="store_true",
+                    help="never run the autotuner: layers the configuration file does not cover use the "
+                         "library default (a profiler trace of such a run holds no tuner launches)")
+    ap.add_argument("--configs", default=os.path.join(ROOT, "paper_2001_00138_amd", "tuned_configs.json"),
+                    help="launch configurations per layer shape, as an earlier --save-configs run wrote "
+                         "them (the tuner's result kept with the layer, as section 5.5 writes it back)")
+    ap.add_argument("--save-configs", default=None,
+                    help="write the launch configurations in use (loaded and tuned) to this JSON file")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-compare", action="store_true")
     ap.add_argument("--no-latency", action="store_true", help="skip the batch-1 stack latency leg")
+    ap.add_argument("--no-other-stacks", action="store_true",
+                    help="skip the per-layer rows of the ResNet-50 / MobileNet-V2 shaped stacks")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the stream-copy and FMA-loop probes")
+    ap.add_argument("--only-timed", action="store_true",
+                    help="the timed region only (for profiler runs): implies every --no-* leg above")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also launch the library's plain copy kernel once on 256 MiB (for rocprofv3 --pmc "
-                         "runs: its FETCH_SIZE / WRITE_SIZE readings calibrate the counters)")
+                    help="also launch the plain copy probe once on 256 MiB (for rocprofv3 --pmc runs: its "
+                         "FETCH_SIZE / WRITE_SIZE readings calibrate the counters)")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "hbm_traffic.json"),
                     help="per-kernel HBM bytes per launch written by profile_summary.py from --pmc runs "
                          "of this same command; fills roofline.traffic when it names the dominant kernel")
@@ -54,10 +75,14 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
               "run it with --gpus 1", file=sys.stderr)
         return 2
+    if args.only_timed:
+        args.no_cpu_baseline = args.no_dense_compare = args.no_latency = True
+        args.no_other_stacks = args.no_peaks = True
 
     import numpy as np
     import torch
     from paper_2001_00138_amd import binding as B
+    from paper_2001_00138_amd import buildlib
     from paper_2001_00138_amd import workloads as wl
 
     if not torch.cuda.is_available():
@@ -65,34 +90,86 @@ def main() -> int:
         return 2
     B.lib()
     torch.cuda.set_device(0)
-    stream = torch.cuda.current_stream()
+    stream = torch.cuda.current_stream()      # the stream every launch below goes to
 
     def variant_name(cfg):
         # variant -1: the library picks its default configuration at every call
         return B.patdnn_variant_name(cfg["variant"]) if cfg["variant"] >= 0 else "auto"
 
-    # ------------------------------------------------------------------ set-up
-    specs = wl.config_layers(args.config)
-    layers = []
-    t_setup = time.time()
-    for li, spec in enumerate(specs):
-        d = wl.gen_layer(args.config, li, n=args.batch, with_input=False)
-        spec = d["spec"]
-        x = torch.empty((spec.n, spec.c_in, spec.h, spec.w), dtype=torch.float32, device="cuda")
-        for i in range(spec.n):
-            x[i].copy_(torch.from_numpy(wl.gen_input_image(spec, args.config, li, i)))
-        L = B.Layer.from_workload(d)
-        bias = torch.from_numpy(d["bias"]).cuda()
-        out = torch.empty(L.output_shape(spec.n, spec.h, spec.w), dtype=torch.float32, device="cuda")
-        kept = int(L.stats()["kept_kernels"])
-        if not args.no_tune:
+    saved = wl.load_tuned_configs(args.configs) if not args.tune else {}
+    used_configs = dict(saved)
+    names = {B.patdnn_variant_name(v): v for v in range(B.patdnn_num_variants())}
+
+    def configure(L, spec, x, bias, out):
+        """Launch configuration of one layer: from the file, tuned now, or the library default."""
+        key = wl.shape_key(spec)
+        c = saved.get(key)
+        if c is not None and c["variant"] in names:
+            L.set_config(names[c["variant"]], c["ck"], c["waves"], c["ksplit"])
+        elif not args.no_tune:
             L.tune(x, bias, out)
         cfg = L.get_config()
-        layers.append(dict(spec=spec, d=d, L=L, x=x, bias=bias, out=out, kept=kept, cfg=cfg,
-                           nz=wl.nz_flops(spec, kept), dense_eq=wl.dense_flops(spec),
-                           bytes=wl.algorithmic_bytes(spec, kept)))
-        _log(f"[setup] {spec.name}: {spec.c_in}->{spec.c_out} @{spec.h} N={spec.n} kept={kept} "
-             f"cfg={cfg} ({variant_name(cfg)})")
+        if cfg["variant"] >= 0:
+            used_configs[key] = dict(cfg, variant=B.patdnn_variant_name(cfg["variant"]))
+        return cfg
+
+    def timed_ms(fn, reps):
+        """Milliseconds of each of `reps` runs of fn() on the stream (HIP events)."""
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for e0, e1 in ev:
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+        torch.cuda.synchronize()
+        return [e0.elapsed_time(e1) for e0, e1 in ev]
+
+    # ------------------------------------------------------------------ set-up
+    def build_stack(cfg_no, batch, per_image_input=True):
+        out = []
+        for li in range(len(wl.config_layers(cfg_no))):
+            d = wl.gen_layer(cfg_no, li, n=batch, with_input=False)
+            spec = d["spec"]
+            x = torch.empty((spec.n, spec.c_in, spec.h, spec.w), dtype=torch.float32, device="cuda")
+            if per_image_input:
+                for i in range(spec.n):
+                    x[i].copy_(torch.from_numpy(wl.gen_input_image(spec, cfg_no, li, i)))
+            else:
+                # the seeded image 0, repeated: the timing does not depend on the values
+                x[:] = torch.from_numpy(wl.gen_input_image(spec, cfg_no, li, 0)).cuda()[None]
+            L = B.Layer.from_workload(d)
+            bias = torch.from_numpy(d["bias"]).cuda()
+            o = torch.empty(L.output_shape(spec.n, spec.h, spec.w), dtype=torch.float32, device="cuda")
+            kept = int(L.stats()["kept_kernels"])
+            cfg = configure(L, spec, x, bias, o)
+            out.append(dict(spec=spec, d=d, L=L, x=x, bias=bias, out=o, kept=kept, cfg=cfg,
+                            nz=wl.nz_flops(spec, kept), dense_eq=wl.dense_flops(spec),
+                            bytes=wl.algorithmic_bytes(spec, kept)))
+            _log(f"[setup] {spec.name}: {spec.c_in}->{spec.c_out} @{spec.h} s{spec.stride} N={spec.n} kept={kept} "
+                 f"cfg={cfg} ({variant_name(cfg)})")
+        return out
+
+    def layer_row(ly, ms_list):
+        spec = ly["spec"]
+        ms_list = sorted(ms_list)
+        med = ms_list[len(ms_list) // 2]
+        t = med * 1e-3
+        bound = "hbm" if (spec.depthwise or ly["bytes"] / PEAK_HBM_GBPS / 1e9 > ly["nz"] / PEAK_FP32_VECTOR_TFLOPS / 1e12) else "alu"
+        return {
+            "layer": spec.name, "shape": f"{spec.c_in}->{spec.c_out}@{spec.h}" + ("/s2" if spec.stride == 2 else ""),
+            "n": spec.n, "kept": ly["kept"], "variant": variant_name(ly["cfg"]),
+            "ck": ly["cfg"]["ck"], "waves": ly["cfg"]["waves"], "ksplit": ly["cfg"]["ksplit"],
+            "ms": round(float(np.mean(ms_list)), 4), "ms_median": round(med, 4), "ms_min": round(ms_list[0], 4),
+            "nz_gflops": round(ly["nz"] / t / 1e9, 1),
+            "dense_eq_gflops": round(ly["dense_eq"] / t / 1e9, 1),
+            "alg_gbps": round(ly["bytes"] / t / 1e9, 1),
+            "bound": bound,
+            "frac_alu_peak": round(ly["nz"] / t / 1e12 / PEAK_FP32_VECTOR_TFLOPS, 4),
+            "frac_alu_nonpacked": round(ly["nz"] / t / 1e12 / PEAK_FP32_NONPACKED_TFLOPS, 4),
+            "frac_hbm_peak": round(ly["bytes"] / t / 1e9 / PEAK_HBM_GBPS, 4),
+        }
+
+    t_setup = time.time()
+    layers = build_stack(args.config, args.batch)
     torch.cuda.synchronize()
     _log(f"[setup] done in {time.time() - t_setup:.1f} s")
 
@@ -104,10 +181,17 @@ def main() -> int:
             if events is not None:
                 events[k][1].record(stream)
 
+    probes = None
+    if args.calibrate_copy or not args.no_peaks:
+        probes = ctypes.CDLL(buildlib.PROBES_LIB)
+        probes.patdnn_probe_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+        probes.patdnn_probe_fma.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p,
+                                            ctypes.POINTER(ctypes.c_double)]
+    sptr = stream.cuda_stream or None
     if args.calibrate_copy:
         src = torch.empty(64 << 20, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)
-        B.patdnn_copy_probe(dst, src)
+        assert probes.patdnn_probe_copy(dst.data_ptr(), src.data_ptr(), src.numel() * 4, sptr) == 0
         torch.cuda.synchronize()
         del src, dst
 
@@ -125,8 +209,8 @@ def main() -> int:
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
-    per_layer_ms = [float(np.mean([ev[s][k][0].elapsed_time(ev[s][k][1]) for s in range(args.steps)]))
-                    for k in range(len(layers))]
+    per_layer = [[ev[s][k][0].elapsed_time(ev[s][k][1]) for s in range(args.steps)] for k in range(len(layers))]
+    per_layer_ms = [float(np.mean(v)) for v in per_layer]
     total_nz = sum(ly["nz"] for ly in layers)
     total_dense = sum(ly["dense_eq"] for ly in layers)
     value = total_nz / (ms_per_step * 1e-3) / 1e9
@@ -161,13 +245,13 @@ def main() -> int:
         }
         # HBM bytes per launch from hardware counters, if a counter run of this command was summarised
         try:
-            vi = next(ly["cfg"]["variant"] for ly in layers if variant_name(ly["cfg"]) == kname)
-            info = B.patdnn_tiled_info(next(ly["L"].handle for ly in layers if variant_name(ly["cfg"]) == kname), vi)
-            sig = (f"Geo<{info['G']}, {info['patch_rows']}, {info['patch_cols']}, {info['conv_stride']}, "
-                   f"{info['lanes_x']}, false,")
+            ly0 = next(ly for ly in layers if variant_name(ly["cfg"]) == kname)
+            info = B.patdnn_tiled_info(ly0["L"].handle, ly0["cfg"]["variant"], ly0["cfg"]["ck"])
+            sig = re.compile(rf"Geo<{info['G']}, {info['patch_rows']}, {info['patch_cols']}, {info['conv_stride']}, "
+                             rf"{info['lanes_x']}, false, \d+, {info['mode']}>, false>")
             with open(args.traffic_json) as f:
                 table = json.load(f)
-            hit = [v for k, v in table.items() if sig in k and "fetch_bytes" in v and "write_bytes" in v]
+            hit = [v for k, v in table.items() if sig.search(k) and "fetch_bytes" in v and "write_bytes" in v]
             if hit:
                 roofline["traffic"] = round(hit[0]["fetch_bytes"] + hit[0]["write_bytes"])
                 roofline["traffic_detail"] = {"fetch_bytes_per_launch": round(hit[0]["fetch_bytes"]),
@@ -176,21 +260,54 @@ def main() -> int:
         except (OSError, ValueError, StopIteration, KeyError, B.PatdnnError):
             pass
 
-    layer_rows = []
-    for k, ly in enumerate(layers):
-        spec = ly["spec"]
-        t = per_layer_ms[k] * 1e-3
-        layer_rows.append({
-            "layer": spec.name, "shape": f"{spec.c_in}->{spec.c_out}@{spec.h}", "kept": ly["kept"],
-            "variant": variant_name(ly["cfg"]),
-            "ck": ly["cfg"]["ck"], "waves": ly["cfg"]["waves"],
-            "ms": round(per_layer_ms[k], 4),
-            "nz_gflops": round(ly["nz"] / t / 1e9, 1),
-            "dense_eq_gflops": round(ly["dense_eq"] / t / 1e9, 1),
-            "alg_gbps": round(ly["bytes"] / t / 1e9, 1),
-            "frac_alu_peak": round(ly["nz"] / t / 1e12 / PEAK_FP32_VECTOR_TFLOPS, 4),
-            "frac_hbm_peak": round(ly["bytes"] / t / 8e12, 4),
-        })
+    layer_rows = [layer_row(ly, per_layer[k]) for k, ly in enumerate(layers)]
+
+    # ------------------------------------------------------------------ peaks measured in this run
+    peaks = None
+    if not args.no_peaks:
+        nbytes = 1 << 30
+        src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        probes.patdnn_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, sptr)
+        ms = sorted(timed_ms(lambda: probes.patdnn_probe_copy(dst.data_ptr(), src.data_ptr(), nbytes, sptr), 10))
+        copy_gbps = 2 * nbytes / (ms[len(ms) // 2] * 1e-3) / 1e9
+        del src, dst
+        sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+        flops = ctypes.c_double()
+        probes.patdnn_probe_fma(sink.data_ptr(), 256 * 32, 4096, sptr, ctypes.byref(flops))
+        ms = sorted(timed_ms(lambda: probes.patdnn_probe_fma(sink.data_ptr(), 256 * 32, 4096, sptr, ctypes.byref(flops)), 10))
+        fma_tflops = flops.value / (ms[len(ms) // 2] * 1e-3) / 1e12
+        peaks = {"stream_copy_gbps": round(copy_gbps, 1), "stream_copy_bytes": 2 * nbytes,
+                 "fma_loop_tflops": round(fma_tflops, 2),
+                 "note": "read + written bytes of a plain 1 GiB device copy; 24 independent plain "
+                         "(non-packed) fp32 FMA chains per lane, 8192 workgroups"}
+        if roofline is not None:
+            roofline["frac_of_measured_fma_loop"] = round(roofline["achieved"] / fma_tflops, 4)
+
+    # ------------------------------------------------------------------ the other stacks, per layer
+    other = None
+    if not args.no_other_stacks and args.config == 5:
+        other = {}
+        for key, cfg_no, batch in (("resnet50_3x3_n1", 3, 1), ("resnet50_3x3_n64", 3, 64),
+                                   ("mobilenet_v2_depthwise_n1", 4, 1), ("mobilenet_v2_depthwise_n64", 4, 64)):
+            try:
+                st = build_stack(cfg_no, batch, per_image_input=False)
+                rows = []
+                for ly in st:
+                    fn = lambda ly=ly: ly["L"].conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+                    fn()
+                    rows.append(layer_row(ly, timed_ms(fn, 20)))
+                tot_ms = sum(r["ms_median"] for r in rows)
+                other[key] = {"workload": wl.CONFIG_NAMES[cfg_no].replace("N=1", f"N={batch}"), "batch": batch,
+                              "layers": rows,
+                              "sum_ms_median": round(tot_ms, 4),
+                              "nz_gflops": round(sum(ly["nz"] for ly in st) / (tot_ms * 1e-3) / 1e9, 1),
+                              "alg_gbps": round(sum(ly["bytes"] for ly in st) / (tot_ms * 1e-3) / 1e9, 1)}
+                for ly in st:
+                    ly["L"].close()
+                del st
+            except Exception as exc:            # the throughput line must not depend on this leg
+                other[key] = {"error": f"{type(exc).__name__}: {exc}"}
 
     # ------------------------------------------------------------------ batch-1 latency of the same stack
     # (the paper's headline scenario, section 6.2: one image through all CONV layers; reported
@@ -199,35 +316,24 @@ def main() -> int:
     if not args.no_latency and args.config == 5:
         def stack_latency(cfg_no):
             """One image through every layer of a configuration, launches back to back."""
-            one = []
-            for li in range(len(wl.config_layers(cfg_no))):
-                d1 = wl.gen_layer(cfg_no, li, n=1, with_input=False)
-                s1 = d1["spec"]
-                x1 = torch.from_numpy(wl.gen_input_image(s1, cfg_no, li, 0)[None]).cuda()
-                L1 = B.Layer.from_workload(d1)
-                b1 = torch.from_numpy(d1["bias"]).cuda()
-                o1 = torch.empty(L1.output_shape(1, s1.h, s1.w), dtype=torch.float32, device="cuda")
-                if not args.no_tune:
-                    L1.tune(x1, b1, o1)
-                one.append((L1, x1, b1, o1, s1, int(L1.stats()["kept_kernels"])))
+            one = build_stack(cfg_no, 1, per_image_input=False)
+            run = lambda: [ly["L"].conv2d(ly["x"], ly["bias"], ly["out"], relu=True) for ly in one]
             for _ in range(3):
-                for L1, x1, b1, o1, _, _ in one:
-                    L1.conv2d(x1, b1, o1, relu=True)
+                run()
             torch.cuda.synchronize()
             reps = 20
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record(stream)
             for _ in range(reps):
-                for L1, x1, b1, o1, _, _ in one:
-                    L1.conv2d(x1, b1, o1, relu=True)
+                run()
             e1.record(stream)
             torch.cuda.synchronize()
             ms1 = e0.elapsed_time(e1) / reps
-            nz1 = sum(wl.nz_flops(s1, k1, n=1) for _, _, _, _, s1, k1 in one)
-            by1 = sum(wl.algorithmic_bytes(s1, k1, n=1) for _, _, _, _, s1, k1 in one)
-            kernels = sorted({variant_name(L1.get_config()) for L1, *_ in one})
-            for L1, *_ in one:
-                L1.close()
+            nz1 = sum(ly["nz"] for ly in one)
+            by1 = sum(ly["bytes"] for ly in one)
+            kernels = sorted({variant_name(ly["L"].get_config()) for ly in one})
+            for ly in one:
+                ly["L"].close()
             return {"workload": wl.CONFIG_NAMES[cfg_no], "layers": len(one), "ms_per_image": round(ms1, 4),
                     "nz_gflops": round(nz1 / (ms1 * 1e-3) / 1e9, 1),
                     "alg_gbps": round(by1 / (ms1 * 1e-3) / 1e9, 1), "kernels": kernels}
@@ -251,14 +357,9 @@ def main() -> int:
                 rows.append({"layer": spec.name, "dense_ms": round(per_layer_ms[k], 4)})
                 continue
             Ld = B.Layer(ly["d"]["weights"], None, None, None, stride=spec.stride, pad=spec.pad, dense=True)
-            Ld.conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(stream)
-            for _ in range(2):
-                Ld.conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
-            e1.record(stream)
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / 2
+            fn = lambda: Ld.conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+            fn()
+            ms = sorted(timed_ms(fn, 3))[1]
             rows.append({"layer": spec.name, "dense_ms": round(ms, 4),
                          "dense_gflops": round(ly["dense_eq"] / (ms * 1e-3) / 1e9, 1),
                          "speedup_pattern_vs_dense": round(ms / per_layer_ms[k], 2)})
@@ -287,6 +388,10 @@ def main() -> int:
                "sample": f"fp64 oracle (OpenMP), all {len(layers)} layers on {images} of the "
                          f"{layers[0]['spec'].n} images, {spent:.1f} s of CPU wall time"}
 
+    if args.save_configs:
+        with open(args.save_configs, "w") as f:
+            json.dump(used_configs, f, indent=1, sort_keys=True)
+
     spec0 = layers[0]["spec"]
     result = {
         "metric": "effective GFLOP/s (non-zero FLOPs) over the pattern-sparse VGG-16 3x3 conv stack",
@@ -299,8 +404,10 @@ def main() -> int:
         "nz_gflop_per_step": round(total_nz / 1e9, 2),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "measured_peaks": peaks,
         "batch1_stack_latency": latency,
         "layers": layer_rows,
+        "other_stacks": other,
         "dense_compare": dense_cmp,
     }
     print(json.dumps(result), flush=True)

@@ -146,9 +146,14 @@ patdnn_status_t patdnn_layout_stats(patdnn_handle_t h, patdnn_stats_t* out);
  *   >0 tiled variants       LDS-staged input tiles, register patches, filter groups
  *                           (section 5.4 load-redundancy elimination); see
  *                           patdnn_variant_name
+ *   after the tiled ones    "dw_p1x4": depthwise layers (groups == c_in), one pass over
+ *                           input and output with 16-byte accesses, four outputs per lane;
+ *                           the default for such layers (section 6.1 evaluates MobileNet-V2)
+ * A configuration set with patdnn_set_config is taken as given or refused
+ * (PATDNN_EUNSUPPORTED), never replaced by another one at launch time.
  * `ck` = input channels staged per LDS pass, `waves` = wavefronts (filter groups)
- * per workgroup; 0 lets the library choose.  `ksplit` > 1 (tiled sparse variants;
- * experimental, needs PATDNN_EXPERIMENTAL=1) cuts the input channels into that many
+ * per workgroup; 0 lets the library choose.  `ksplit` > 1 (tiled sparse variants)
+ * cuts the input channels into that many
  * slices handled by different workgroups, whose partial sums are added into the output
  * with atomic adds between a zero-fill and a bias + ReLU kernel (three launches; the
  * summation order then varies from run to run within fp32 rounding); 0 or 1 = off.
@@ -237,15 +242,6 @@ patdnn_status_t patdnn_export_tiled(patdnn_handle_t h, int32_t variant, int32_t 
                                     int32_t* slot_channel,   /* [num_groups*G] */
                                     uint32_t* chunk_ptr,     /* [num_groups*num_chunks] */
                                     uint32_t* steps);        /* [num_steps*24] */
-
-/*
- * Measurement aid, not part of the method: copies `bytes` (a multiple of 16; both
- * pointers DEVICE, 16-byte aligned, not overlapping) with a plain kernel,
- * asynchronously on `stream`.  Profiled beside the convolution kernels it calibrates
- * hardware traffic counters: it reads and writes exactly `bytes`.  PATDNN_EINVAL on
- * a null / misaligned pointer or size, PATDNN_EHIP if the launch fails.
- */
-patdnn_status_t patdnn_copy_probe(void* dst, const void* src, size_t bytes, void* stream);
 
 /*
  * Device self-test behind the variants with threaded dispatch: checks on the current

@@ -25,7 +25,7 @@ EXPORTS = [
     "patdnn_encode", "patdnn_conv2d", "patdnn_output_shape", "patdnn_decode",
     "patdnn_export_fkw", "patdnn_layout_stats", "patdnn_num_variants", "patdnn_variant_name",
     "patdnn_set_config", "patdnn_get_config", "patdnn_tune", "patdnn_tiled_info",
-    "patdnn_export_tiled", "patdnn_copy_probe", "patdnn_selftest", "patdnn_destroy",
+    "patdnn_export_tiled", "patdnn_selftest", "patdnn_destroy",
     "patdnn_status_string", "patdnn_last_error",
 ]
 
@@ -96,7 +96,6 @@ def lib() -> ctypes.CDLL:
         L.patdnn_tune.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_float)]
         L.patdnn_tiled_info.argtypes = [vp, i32, i32, ctypes.POINTER(TiledInfo)]
         L.patdnn_export_tiled.argtypes = [vp, i32, i32, vp, vp, vp]
-        L.patdnn_copy_probe.argtypes = [vp, vp, ctypes.c_size_t, vp]
         L.patdnn_selftest.argtypes = []
         L.patdnn_destroy.argtypes = [vp]
         L.patdnn_destroy.restype = None
@@ -263,15 +262,6 @@ def patdnn_export_tiled(handle: int, variant: int, ck: int = 0) -> dict:
     _check(lib().patdnn_export_tiled(handle, variant, ck, out["slot_channel"].ctypes.data,
                                      out["chunk_ptr"].ctypes.data, out["steps"].ctypes.data))
     return out
-
-
-def patdnn_copy_probe(dst, src, *, stream=None) -> None:
-    """Plain device copy of ``src`` into ``dst`` (same byte size, a multiple of 16): the
-    known-size kernel that calibrates traffic counters."""
-    nbytes = src.numel() * src.element_size()
-    if dst.numel() * dst.element_size() != nbytes:
-        raise ValueError("dst and src must have the same byte size")
-    _check(lib().patdnn_copy_probe(_devptr(dst), _devptr(src), nbytes, _stream_ptr(stream)))
 
 
 def patdnn_selftest() -> None:

@@ -17,7 +17,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libpatdnn.so")
-SOURCES = ["patdnn_api.hip", "kernel_fkw.hip", "kernel_tiled.hip", "copy_probe.hip", "selftest.hip", "encoder.cpp"]
+PROBES_LIB = os.path.join(HERE, "libpatdnn_probes.so")     # bench-side measurement probes
+SOURCES = ["patdnn_api.hip", "kernel_fkw.hip", "kernel_dw.hip", "kernel_tiled.hip", "selftest.hip", "encoder.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -69,8 +70,14 @@ def build(verbose: bool = False) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stderr}")
+    # the measurement probes bench.py times beside the kernels: a library of their own
+    probe_obj = _compile("bench_probes.hip")
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", PROBES_LIB, probe_obj],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"link failed:\n{r.stderr}")
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB} and {PROBES_LIB}")
     return LIB
 
 

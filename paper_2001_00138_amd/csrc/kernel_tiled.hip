@@ -404,6 +404,8 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
 #endif
     const long long blocks = tiles * a.fgsets;
     if (bands > INT32_MAX || blocks > INT32_MAX) return hipErrorInvalidValue;
+    // every dword of a staged channel needs a staging slot of some thread
+    if ((long long)waves * 64 * GEO::MAXSLOTS < GEO::TILEP || waves < 1 || waves > 8) return hipErrorInvalidValue;
     const size_t lds_bytes = ((GEO::MODE & 16) ? 1 : 2) * (size_t)t.ck * GEO::TILEP * sizeof(float);   // staging buffers
     if (lds_bytes > 64 * 1024) {
         static std::atomic<uint64_t> allowed{0};

@@ -24,6 +24,10 @@ struct DevFkw {
     const uint16_t* masks = nullptr;
     int32_t num_patterns = 0;
     int32_t taps = 4;
+    // depthwise layers: per stored filter, the pattern mask of its one kernel (0 if the
+    // kernel was removed) and its four weights
+    const int32_t* dw_mask = nullptr;
+    const float* dw_weight = nullptr;
 };
 
 // Filter-group layout on the device: record streams (sparse) or 9-tap weights (dense).
@@ -41,6 +45,10 @@ struct DevTiled {
 // Filter-major walk of the FKW arrays, one lane per output pixel.
 hipError_t launch_fkw(const DevFkw& f, const ConvShape& s, const float* in, const float* bias,
                       float* out, hipStream_t stream);
+
+// Depthwise layers: one pass over input and output, 16-byte accesses, four outputs per lane.
+hipError_t launch_dw(const DevFkw& f, const ConvShape& s, const float* in, const float* bias,
+                     float* out, hipStream_t stream);
 
 // ---------------------------------------------------------------------------
 // Tiled kernels: compile-time geometry per variant, run-time launch parameters.

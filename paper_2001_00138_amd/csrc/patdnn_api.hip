@@ -113,6 +113,12 @@ bool variant_selectable(const patdnn_layer* h, const TiledVariant& v)
     return variant_fits_layer(h, v) && !v.experimental;
 }
 
+// Variant numbers: 0 the FKW walk, 1..T the tiled variants, then the kernels below.
+enum ExtraVariant { kExtraDepthwise = 0, kNumExtra };
+int extra_variant(int variant) { return variant - 1 - num_tiled_variants(); }     // < 0: not one
+int variant_of_extra(int extra) { return 1 + num_tiled_variants() + extra; }
+const char* const kExtraNames[kNumExtra] = {"dw_p1x4"};
+
 constexpr int kMaxLdsBytes = 160 * 1024;      // LDS of one CU; two staging buffers must fit
 constexpr int kMaxWaves = 8;
 
@@ -211,6 +217,11 @@ patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const Conv
         hipError_t e = launch_fkw(h->dfkw, s, in, bias, out, stream);
         return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching the FKW kernel");
     }
+    if (extra_variant(c.variant) == kExtraDepthwise) {
+        if (!h->L.depthwise) return fail(PATDNN_EUNSUPPORTED, "the depthwise kernel runs depthwise layers only");
+        hipError_t e = launch_dw(h->dfkw, s, in, bias, out, stream);
+        return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching the depthwise kernel");
+    }
     const int vi = c.variant - 1;
     if (vi < 0 || vi >= num_tiled_variants()) return fail(PATDNN_EINVAL, "no such variant");
     const TiledVariant& v = tiled_variant(vi);
@@ -237,6 +248,7 @@ patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const Conv
 // The configuration used when the caller has not chosen or tuned one.
 patdnn_config_t default_config(patdnn_layer* h, const ConvShape& s)
 {
+    if (h->L.depthwise) return patdnn_config_t{variant_of_extra(kExtraDepthwise), 0, 0, 1};
     for (int vi = 0; vi < num_tiled_variants(); ++vi) {
         const TiledVariant& v = tiled_variant(vi);
         if (!variant_selectable(h, v)) continue;
@@ -280,6 +292,22 @@ patdnn_status_t patdnn_encode(const patdnn_layer_desc_t* desc, const float* dens
             return hip_fail(e, "uploading the FKW arrays");
         h->dfkw.num_patterns = f.num_patterns;
         h->dfkw.taps = f.taps;
+        if (h->L.depthwise) {
+            // per stored filter: the mask of its kernel's pattern and its four weights
+            const int c = desc->c_out, P = f.num_patterns;
+            std::vector<int32_t> dmask((size_t)c, 0);
+            std::vector<float> dweight((size_t)c * 4, 0.0f);
+            for (int s = 0; s < c; ++s) {
+                if (f.offset[s + 1] == f.offset[s]) continue;
+                const int32_t* st = &f.stride[(size_t)s * (P + 1)];
+                for (int p = 0; p < P; ++p)
+                    if (st[p + 1] > st[p]) dmask[s] = f.masks[p];
+                for (int t = 0; t < 4; ++t) dweight[(size_t)s * 4 + t] = f.weight[(size_t)f.offset[s] * 4 + t];
+            }
+            if ((e = upload(h->allocations, dmask, &h->dfkw.dw_mask)) != hipSuccess ||
+                (e = upload(h->allocations, dweight, &h->dfkw.dw_weight)) != hipSuccess)
+                return hip_fail(e, "uploading the depthwise arrays");
+        }
         h->on_device = true;
     }
     // build (and upload) the group layout of the default variant; the layouts of the other
@@ -429,12 +457,13 @@ patdnn_status_t patdnn_layout_stats(patdnn_handle_t h, patdnn_stats_t* out)
     return PATDNN_OK;
 }
 
-int32_t patdnn_num_variants(void) { return 1 + num_tiled_variants(); }
+int32_t patdnn_num_variants(void) { return 1 + num_tiled_variants() + kNumExtra; }
 
 const char* patdnn_variant_name(int32_t variant)
 {
     if (variant == PATDNN_VARIANT_FKW) return "fkw";
-    if (variant < 0 || variant > num_tiled_variants()) return nullptr;
+    if (variant < 0 || variant >= patdnn_num_variants()) return nullptr;
+    if (extra_variant(variant) >= 0) return kExtraNames[extra_variant(variant)];
     return tiled_variant(variant - 1).name;
 }
 
@@ -446,7 +475,13 @@ patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
         h->cfg_tuned = false;
         return PATDNN_OK;
     }
-    if (cfg->variant > num_tiled_variants()) return fail(PATDNN_EINVAL, "no such variant");
+    if (cfg->variant >= patdnn_num_variants()) return fail(PATDNN_EINVAL, "no such variant");
+    if (extra_variant(cfg->variant) == kExtraDepthwise) {
+        if (!h->L.depthwise) return fail(PATDNN_EUNSUPPORTED, "the depthwise kernel runs depthwise layers only");
+        h->cfg = patdnn_config_t{cfg->variant, 0, 0, 1};
+        h->cfg_tuned = false;
+        return PATDNN_OK;
+    }
     if (cfg->variant > 0) {
         const TiledVariant& v = tiled_variant(cfg->variant - 1);
         if (!variant_fits_layer(h, v)) return fail(PATDNN_EUNSUPPORTED, "variant cannot run this layer");
@@ -522,8 +557,9 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
                 if (w2 > 1 && w2 / 2 >= groups) continue;      // mostly idle wavefronts
                 if (!resolve_tiled_params(h, v, s, ck2, w2)) continue;
                 const int num_chunks = (s.c_in + ck2 - 1) / ck2;
-                for (int ks : {1, 2, 4}) {
-                    if (ks > 1 && (v.dense || ks > num_chunks || wavefronts * (ks / 2) >= 3 * kWaveSlots)) continue;
+                for (int ks : {1, 2, 3, 4, 6, 8}) {
+                    // slices only while the launch before this split leaves wavefront slots empty
+                    if (ks > 1 && (v.dense || ks > num_chunks || wavefronts * (ks - 1) >= 2 * kWaveSlots)) continue;
                     patdnn_config_t c{vi + 1, ck2, w2, ks};
                     bool dup = false;
                     for (const auto& o : cands)
@@ -532,6 +568,7 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
                 }
             }
     }
+    if (h->L.depthwise) cands.push_back(patdnn_config_t{variant_of_extra(kExtraDepthwise), 0, 0, 1});
     cands.push_back(patdnn_config_t{PATDNN_VARIANT_FKW, 0, 0, 1});
 
     hipEvent_t e0, e1;
@@ -602,6 +639,8 @@ static patdnn_status_t find_tiled(patdnn_handle_t h, int32_t variant, int32_t ck
 {
     if (!h) return fail(PATDNN_EINVAL, "handle is NULL");
     const int vi = variant - 1;
+    if (extra_variant(variant) >= 0 && variant < patdnn_num_variants())
+        return fail(PATDNN_EUNSUPPORTED, "this variant has no filter-group layout");
     if (vi < 0 || vi >= num_tiled_variants()) return fail(PATDNN_EINVAL, "not a tiled variant");
     const TiledVariant& v = tiled_variant(vi);
     if (v.dense || !variant_fits_layer(h, v)) return fail(PATDNN_EUNSUPPORTED, "variant cannot run this layer");

@@ -274,3 +274,25 @@ def algorithmic_bytes(spec: LayerSpec, kept: int, n: Optional[int] = None) -> in
     act = 4 * n * (spec.c_in * spec.h * spec.w + spec.c_out * spec.h_out * spec.w_out)
     per_kernel = 36 if spec.dense else 18
     return act + per_kernel * kept + 4 * spec.c_out
+
+
+# ---------------------------------------------------------------------------
+# launch configurations kept with the layer shapes (section 5.5: the tuner's result is
+# written back into the layer's description).  Plain data: names and numbers.
+# ---------------------------------------------------------------------------
+
+def shape_key(spec: LayerSpec) -> str:
+    kind = "dw" if spec.depthwise else ("dense" if spec.dense else "sparse")
+    return f"{kind}:{spec.c_in}->{spec.c_out}@{spec.h}x{spec.w}:s{spec.stride}p{spec.pad}:n{spec.n}"
+
+
+def load_tuned_configs(path: str) -> dict:
+    """{shape_key: {"variant": name, "ck": .., "waves": .., "ksplit": ..}}; {} if the file is absent."""
+    import json
+    try:
+        with open(path) as f:
+            table = json.load(f)
+    except OSError:
+        return {}
+    return {k: v for k, v in table.items()
+            if isinstance(v, dict) and {"variant", "ck", "waves", "ksplit"} <= set(v)}

@@ -148,5 +148,6 @@ long hostmodel_run(int variant, int G, int num_groups, int ck, int num_chunks, c
 }
 
 int hostmodel_variant_lds_floats(int variant) { return patdnn::tiled_variant(variant).lds_floats_per_channel; }
+int hostmodel_variant_max_slots(int variant) { return patdnn::tiled_variant(variant).max_slots; }
 
 }  // extern "C"

@@ -21,8 +21,8 @@ def _built():
         buildlib.build()
 
 
-def _header_functions():
-    text = open(os.path.join(ROOT, "include", "patdnn.h")).read()
+def _header_functions(header="patdnn.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(patdnn_[a-z0-9_]+)\s*\(", text)))
 
@@ -37,6 +37,17 @@ def test_library_exports_every_declared_symbol():
     assert B.patdnn_num_variants() >= 2
     assert B.patdnn_variant_name(0) == "fkw"
     assert B.patdnn_variant_name(B.patdnn_num_variants()) is None
+
+
+def test_probe_library_exports_every_declared_symbol():
+    """The bench-side probes live in a library of their own with a header of their own."""
+    import ctypes
+    from paper_2001_00138_amd import buildlib
+    names = _header_functions("patdnn_probes.h")
+    assert names == ["patdnn_probe_copy", "patdnn_probe_fma"]
+    L = ctypes.CDLL(buildlib.PROBES_LIB)
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in patdnn_probes.h but not exported"
 
 
 def _host_layer(layer, **kw):

@@ -129,7 +129,7 @@ def test_every_sparse_variant_on_the_host_model(hostmodel, oracle, case):
             assert e.status == B.PATDNN_EUNSUPPORTED
             continue
         lds_per_channel = hostmodel.hostmodel_variant_lds_floats(v - 1)
-        min_waves = -(-lds_per_channel // (64 * 16))        # enough staging slots for any compiled variant
+        min_waves = -(-lds_per_channel // (64 * hostmodel.hostmodel_variant_max_slots(v - 1)))   # staging slots
         for ksplit in (1, min(3, t["num_chunks"])):
             got = _run(hostmodel, v, t, x, bias, case["pad"], stride, True, max(case["waves"], min_waves, 3),
                        case["c_out"], ksplit=ksplit)
@@ -172,7 +172,7 @@ def test_default_variant_over_the_tuner_grid(hostmodel, oracle, ck, waves):
     names = {B.patdnn_variant_name(v): v for v in range(1, B.patdnn_num_variants())}
     for v in (names["t_g16_p7x1_s1_x16"], names["t_g8_p7x2_s1_x8_thw1b"]):   # call and threaded dispatch
         t = L.export_tiled(v, ck)
-        min_waves = -(-hostmodel.hostmodel_variant_lds_floats(v - 1) // (64 * 7))
+        min_waves = -(-hostmodel.hostmodel_variant_lds_floats(v - 1) // (64 * hostmodel.hostmodel_variant_max_slots(v - 1)))
         got = _run(hostmodel, v, t, x, bias, 1, 1, True, max(waves, min_waves), c_out)
         assert not np.isnan(got).any()
         assert float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max()) <= TOL
