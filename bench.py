@@ -338,7 +338,42 @@ def main() -> int:
                     "nz_gflops": round(nz1 / (ms1 * 1e-3) / 1e9, 1),
                     "alg_gbps": round(by1 / (ms1 * 1e-3) / 1e9, 1), "kernels": kernels}
 
+        def vgg_chained():
+            """The VGG-16 shaped stack as a network: every layer reads what the one before wrote,
+            ReLU + 2x2 max pooling fused into conv 2, 4, 7, 10 and 13; plain launches and one HIP
+            graph launch per image (patdnn_stack_run)."""
+            one = build_stack(2, 1, per_image_input=False)
+            pool = [li in (1, 3, 6, 9, 12) for li in range(len(one))]
+            st = B.Stack([(ly["L"], ly["bias"], True, p) for ly, p in zip(one, pool)], 1, one[0]["spec"].h,
+                         one[0]["spec"].w)
+            out = torch.empty(st.output_shape(), dtype=torch.float32, device="cuda")
+            side = torch.cuda.Stream()
+            res = {}
+            with torch.cuda.stream(side):
+                for key, graph in (("plain_ms_per_image", False), ("graph_ms_per_image", True)):
+                    for _ in range(3):
+                        st.run(one[0]["x"], out, graph=graph, stream=side)
+                    side.synchronize()
+                    reps = 50
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(side)
+                    for _ in range(reps):
+                        st.run(one[0]["x"], out, graph=graph, stream=side)
+                    e1.record(side)
+                    side.synchronize()
+                    res[key] = round(e0.elapsed_time(e1) / reps, 4)
+            st.close()
+            for ly in one:
+                ly["L"].close()
+            res["note"] = ("13 layers chained on real activations, 5 fused ReLU + 2x2 max-pool epilogues "
+                           "(18 kernel launches per image); the graph run is one hipGraphLaunch")
+            return res
+
         latency = {"note": "one image, all layers launched back to back on one stream, launch gaps included"}
+        try:
+            latency["vgg16_chained"] = vgg_chained()
+        except Exception as exc:
+            latency["vgg16_chained"] = {"error": f"{type(exc).__name__}: {exc}"}
         for key, cfg_no in (("vgg16", 2), ("resnet50_3x3", 3), ("mobilenet_v2_depthwise", 4)):
             try:
                 latency[key] = stack_latency(cfg_no)

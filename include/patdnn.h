@@ -96,6 +96,20 @@ patdnn_status_t patdnn_conv2d(patdnn_handle_t h, const float* input, int32_t n, 
                               int32_t w_in, const float* bias, float* output,
                               int32_t fuse_relu, void* stream);
 
+/*
+ * The layer followed by ReLU and 2x2 max pooling with stride 2 (an odd last row / column
+ * is dropped), fused: the CONV stages of the networks the paper runs end in a pooling
+ * layer (section 2.1, section 6.2) and only the pooled tensor is written.
+ *   output  DEVICE [n][c_out][h_out/2][w_out/2]; must not overlap input
+ * Two launches on `stream` (a kernel that zeroes the output, then the layer, whose lanes
+ * fold their values into the pooled cells with integer atomic max on the float bits:
+ * exact and independent of the order).  Otherwise as patdnn_conv2d.  Depthwise layers:
+ * PATDNN_EUNSUPPORTED.  A layer whose configuration splits the input channels runs its
+ * default configuration here.
+ */
+patdnn_status_t patdnn_conv2d_pool(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
+                                   int32_t w_in, const float* bias, float* output, void* stream);
+
 /* out_nchw = {n, c_out, h_out, w_out}; PATDNN_EINVAL if the output would be empty. */
 patdnn_status_t patdnn_output_shape(patdnn_handle_t h, int32_t n, int32_t h_in, int32_t w_in,
                                     int32_t out_nchw[4]);
@@ -255,6 +269,36 @@ patdnn_status_t patdnn_export_tiled(patdnn_handle_t h, int32_t variant, int32_t 
 patdnn_status_t patdnn_selftest(void);
 
 void        patdnn_destroy(patdnn_handle_t h);          /* NULL is a no-op */
+
+/*
+ * A stack of layers run back to back on one stream - the paper's headline scenario, one
+ * image through all CONV layers of a network (section 6.2).  Layer i reads what layer
+ * i-1 wrote; `pool2` fuses ReLU + 2x2 max pooling into the layer (as patdnn_conv2d_pool).
+ * The stack owns two DEVICE buffers for the tensors between layers (allocated by
+ * patdnn_stack_create, freed by patdnn_stack_destroy); handles and bias arrays stay the
+ * caller's and must outlive the stack.
+ *   patdnn_stack_run, use_graph == 0: every launch goes to `stream` directly.
+ *   use_graph != 0: the launches are recorded once into a HIP graph (stream capture on
+ *   `stream`, which must not be the default stream; preceded by one plain run the first
+ *   time) and replayed with a single graph launch on every later call with the same
+ *   input / output addresses; other addresses record again.  No memset node is recorded:
+ *   buffers are cleared by kernels.
+ * Asynchronous; calls on one stack must not overlap.
+ */
+typedef struct patdnn_stack* patdnn_stack_t;
+typedef struct {
+    patdnn_handle_t layer;
+    const float* bias;       /* DEVICE [c_out] or NULL */
+    int32_t fuse_relu;
+    int32_t pool2;           /* ReLU + 2x2 max pooling after the layer (implies fuse_relu) */
+} patdnn_stack_layer_t;
+
+patdnn_status_t patdnn_stack_create(const patdnn_stack_layer_t* layers, int32_t num_layers, int32_t n,
+                                    int32_t h_in, int32_t w_in, patdnn_stack_t* out);
+patdnn_status_t patdnn_stack_output_shape(patdnn_stack_t s, int32_t out_nchw[4]);
+patdnn_status_t patdnn_stack_run(patdnn_stack_t s, const float* input, float* output,   /* DEVICE */
+                                 int32_t use_graph, void* stream);
+void            patdnn_stack_destroy(patdnn_stack_t s);     /* NULL is a no-op */
 const char* patdnn_status_string(patdnn_status_t s);
 const char* patdnn_last_error(void);
 

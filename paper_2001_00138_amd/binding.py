@@ -22,7 +22,8 @@ PATDNN_DENSE, PATDNN_STRICT, PATDNN_HOST_ONLY = 1, 2, 4
 PATDNN_VARIANT_FKW = 0
 
 EXPORTS = [
-    "patdnn_encode", "patdnn_conv2d", "patdnn_output_shape", "patdnn_decode",
+    "patdnn_encode", "patdnn_conv2d", "patdnn_conv2d_pool", "patdnn_output_shape", "patdnn_decode",
+    "patdnn_stack_create", "patdnn_stack_output_shape", "patdnn_stack_run", "patdnn_stack_destroy",
     "patdnn_export_fkw", "patdnn_layout_stats", "patdnn_num_variants", "patdnn_variant_name",
     "patdnn_set_config", "patdnn_get_config", "patdnn_tune", "patdnn_tiled_info",
     "patdnn_export_tiled", "patdnn_selftest", "patdnn_destroy",
@@ -64,6 +65,11 @@ class TiledInfo(ctypes.Structure):
                 ("mode", ctypes.c_int32)]
 
 
+class StackLayer(ctypes.Structure):
+    _fields_ = [("layer", ctypes.c_void_p), ("bias", ctypes.c_void_p), ("fuse_relu", ctypes.c_int32),
+                ("pool2", ctypes.c_int32)]
+
+
 class PatdnnError(RuntimeError):
     def __init__(self, status: int, text: str):
         super().__init__(f"patdnn status {status}: {text}")
@@ -84,6 +90,12 @@ def lib() -> ctypes.CDLL:
         vp, i32 = ctypes.c_void_p, ctypes.c_int32
         L.patdnn_encode.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, ctypes.POINTER(vp)]
         L.patdnn_conv2d.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp]
+        L.patdnn_conv2d_pool.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+        L.patdnn_stack_create.argtypes = [ctypes.POINTER(StackLayer), i32, i32, i32, i32, ctypes.POINTER(vp)]
+        L.patdnn_stack_output_shape.argtypes = [vp, ctypes.POINTER(i32 * 4)]
+        L.patdnn_stack_run.argtypes = [vp, vp, vp, i32, vp]
+        L.patdnn_stack_destroy.argtypes = [vp]
+        L.patdnn_stack_destroy.restype = None
         L.patdnn_output_shape.argtypes = [vp, i32, i32, i32, ctypes.POINTER(i32 * 4)]
         L.patdnn_decode.argtypes = [vp, vp, vp, vp]
         L.patdnn_export_fkw.argtypes = [vp, vp, vp, vp, vp, vp]
@@ -192,6 +204,60 @@ def patdnn_conv2d(handle: int, x, bias=None, out=None, *, fuse_relu=False, strea
     return out
 
 
+def patdnn_conv2d_pool(handle: int, x, bias=None, out=None, *, stream=None):
+    """conv + bias + ReLU + 2x2 max pooling, fused.  Returns ``out`` [n][c_out][h_out/2][w_out/2]."""
+    import torch
+    if x.dtype != torch.float32 or x.dim() != 4:
+        raise ValueError("input must be a 4-d float32 tensor")
+    n, _, h_in, w_in = x.shape
+    full = patdnn_output_shape(handle, n, h_in, w_in)
+    shape = (full[0], full[1], full[2] // 2, full[3] // 2)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=x.device)
+    elif tuple(out.shape) != shape or out.dtype != torch.float32:
+        raise ValueError(f"output must be float32 {shape}")
+    _check(lib().patdnn_conv2d_pool(handle, _devptr(x), n, h_in, w_in, _devptr(bias), _devptr(out),
+                                    _stream_ptr(stream)))
+    return out
+
+
+class Stack:
+    """patdnn_stack_*: layers run back to back; ``layers`` = [(Layer, bias tensor or None, relu, pool2)]."""
+
+    def __init__(self, layers, n: int, h_in: int, w_in: int):
+        self._keep = list(layers)               # handles and bias tensors must outlive the stack
+        arr = (StackLayer * len(layers))()
+        for i, (L, bias, relu, pool) in enumerate(layers):
+            arr[i] = StackLayer(L.handle, _devptr(bias), int(bool(relu)), int(bool(pool)))
+        h = ctypes.c_void_p()
+        _check(lib().patdnn_stack_create(arr, len(layers), n, h_in, w_in, ctypes.byref(h)))
+        self.handle = h.value
+
+    def output_shape(self):
+        out = (ctypes.c_int32 * 4)()
+        _check(lib().patdnn_stack_output_shape(self.handle, ctypes.byref(out)))
+        return tuple(out)
+
+    def run(self, x, out=None, *, graph=False, stream=None):
+        import torch
+        if out is None:
+            out = torch.empty(self.output_shape(), dtype=torch.float32, device=x.device)
+        _check(lib().patdnn_stack_run(self.handle, _devptr(x), _devptr(out), int(bool(graph)),
+                                      _stream_ptr(stream)))
+        return out
+
+    def close(self):
+        if self.handle:
+            lib().patdnn_stack_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
 def patdnn_layout_stats(handle: int) -> dict:
     s = Stats()
     _check(lib().patdnn_layout_stats(handle, ctypes.byref(s)))
@@ -297,6 +363,9 @@ class Layer:
 
     def conv2d(self, x, bias=None, out=None, *, relu=False, stream=None):
         return patdnn_conv2d(self.handle, x, bias, out, fuse_relu=relu, stream=stream)
+
+    def conv2d_pool(self, x, bias=None, out=None, *, stream=None):
+        return patdnn_conv2d_pool(self.handle, x, bias, out, stream=stream)
 
     def output_shape(self, n, h, w):
         return patdnn_output_shape(self.handle, n, h, w)

@@ -18,7 +18,7 @@ struct FkwArgs {
     const float* bias;
     float* out;
     int32_t num_patterns;
-    int32_t n, c_in, c_out, h, w, ho, wo, conv_stride, pad, relu;
+    int32_t n, c_in, c_out, h, w, ho, wo, conv_stride, pad, relu, pool;
 };
 
 template <int TAPS>
@@ -65,6 +65,15 @@ __global__ __launch_bounds__(256) void fkw_conv_kernel(FkwArgs a)
             }
         }
         if (a.bias) acc += a.bias[co];
+        if (a.pool) {
+            // ReLU + 2x2 max pooling folded into the (zeroed) pooled output
+            const int pho = a.ho >> 1, pwo = a.wo >> 1;
+            if (live && acc > 0.0f && (oh >> 1) < pho && (ow >> 1) < pwo)
+                atomicMax(reinterpret_cast<unsigned*>(a.out) + ((size_t)img * a.c_out + co) * ((size_t)pho * pwo) +
+                              (size_t)(oh >> 1) * pwo + (ow >> 1),
+                          __float_as_uint(acc));
+            continue;
+        }
         if (a.relu) acc = fmaxf(acc, 0.0f);
         if (live) a.out[((size_t)img * a.c_out + co) * a.ho * a.wo + pix] = acc;
     }
@@ -74,7 +83,7 @@ hipError_t launch_fkw(const DevFkw& f, const ConvShape& s, const float* in, cons
                       float* out, hipStream_t stream)
 {
     FkwArgs a{f.offset, f.reorder, f.index, f.stride, f.weight, f.masks, in, bias, out,
-              f.num_patterns, s.n, s.c_in, s.c_out, s.h, s.w, s.ho, s.wo, s.stride, s.pad, s.relu};
+              f.num_patterns, s.n, s.c_in, s.c_out, s.h, s.w, s.ho, s.wo, s.stride, s.pad, s.relu, s.pool};
     const unsigned px_blocks = (unsigned)(((long long)s.ho * s.wo + 255) / 256);
     unsigned filters_left = (unsigned)s.c_out;
     // gridDim.y is limited to 65535: walk the filters in slabs

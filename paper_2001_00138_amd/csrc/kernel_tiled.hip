@@ -43,7 +43,7 @@ struct TiledArgs {
     const uint32_t* chunk_ptr;
     const uint32_t* steps;
     const float* w9;
-    int32_t n, c_in, c_out, h, w, ho, wo, pad, relu;
+    int32_t n, c_in, c_out, h, w, ho, wo, pad, relu, pool;
     int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets;
 #ifdef PATDNN_TIMELINE
     unsigned long long* tl;      // [blocks][8 waves][8 phases] cycle totals (debug builds only)
@@ -314,25 +314,46 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     // ---- epilogue: bias, ReLU, scatter to the original output channel
     if (group_ok && band_ok) {
         const size_t oplane = (size_t)a.ho * a.wo;
+        if (!SPLITK && a.pool) {
+            // ReLU + 2x2 max pooling: fold every value into its pooled cell (zero beforehand)
+            const int pho = a.ho >> 1, pwo = a.wo >> 1;
 #pragma unroll
-        for (int s = 0; s < G; ++s) {
-            const int co = load_uniform(a.slot_channel, group * G + s);
-            if (co < 0) continue;
-            const float b = a.bias ? load_uniform(a.bias, co) : 0.0f;
-            float* dst = a.out + ((size_t)img * a.c_out + co) * oplane;
+            for (int s = 0; s < G; ++s) {
+                const int co = load_uniform(a.slot_channel, group * G + s);
+                if (co < 0) continue;
+                const float b = a.bias ? load_uniform(a.bias, co) : 0.0f;
+                unsigned* dst = reinterpret_cast<unsigned*>(a.out) + ((size_t)img * a.c_out + co) * ((size_t)pho * pwo);
 #pragma unroll
-            for (int r = 0; r < PR; ++r)
+                for (int r = 0; r < PR; ++r)
 #pragma unroll
-                for (int c = 0; c < PC; ++c) {
-                    const int oy = oy0 + r, ox = ox0 + c;
-                    if constexpr (SPLITK) {
-                        if (oy < a.ho && ox < a.wo) unsafeAtomicAdd(&dst[(size_t)oy * a.wo + ox], acc[s][r * PC + c]);
-                    } else {
-                        float v = acc[s][r * PC + c] + b;
-                        if (a.relu) v = fmaxf(v, 0.0f);
-                        if (oy < a.ho && ox < a.wo) dst[(size_t)oy * a.wo + ox] = v;
+                    for (int c = 0; c < PC; ++c) {
+                        const int oy = oy0 + r, ox = ox0 + c;
+                        const float v = acc[s][r * PC + c] + b;
+                        if (v > 0.0f && (oy >> 1) < pho && (ox >> 1) < pwo)
+                            atomicMax(&dst[(size_t)(oy >> 1) * pwo + (ox >> 1)], __float_as_uint(v));
                     }
-                }
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < G; ++s) {
+                const int co = load_uniform(a.slot_channel, group * G + s);
+                if (co < 0) continue;
+                const float b = a.bias ? load_uniform(a.bias, co) : 0.0f;
+                float* dst = a.out + ((size_t)img * a.c_out + co) * oplane;
+#pragma unroll
+                for (int r = 0; r < PR; ++r)
+#pragma unroll
+                    for (int c = 0; c < PC; ++c) {
+                        const int oy = oy0 + r, ox = ox0 + c;
+                        if constexpr (SPLITK) {
+                            if (oy < a.ho && ox < a.wo) unsafeAtomicAdd(&dst[(size_t)oy * a.wo + ox], acc[s][r * PC + c]);
+                        } else {
+                            float v = acc[s][r * PC + c] + b;
+                            if (a.relu) v = fmaxf(v, 0.0f);
+                            if (oy < a.ho && ox < a.wo) dst[(size_t)oy * a.wo + ox] = v;
+                        }
+                    }
+            }
         }
     }
 #ifdef PATDNN_TIMELINE
@@ -380,17 +401,35 @@ static hipError_t allow_big_lds(const void* fn, std::atomic<uint64_t>& done)
     return e;
 }
 
+// out[n][c][py][px] = max over the 2x2 window of relu(sum[n][c][2py+dy][2px+dx] + bias[c]):
+// finishes a split-channel launch whose partial sums were added up in `sum`
+__global__ __launch_bounds__(256) void bias_relu_pool_kernel(const float* sum, const float* bias, float* out,
+                                                             int c_out, int ho, int wo, int pho, int pwo, size_t total)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int px = (int)(i % pwo);
+        size_t r = i / pwo;
+        const int py = (int)(r % pho);
+        r /= pho;                                   // n * c_out + c
+        const float b = bias ? bias[r % (size_t)c_out] : 0.0f;
+        const float* src = sum + (r * ho + 2 * py) * (size_t)wo + 2 * px;
+        const float m = fmaxf(fmaxf(src[0], src[1]), fmaxf(src[wo], src[wo + 1]));
+        out[i] = fmaxf(m + b, 0.0f);
+    }
+}
+
 template <class GEO>
 static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const float* in,
                                const float* bias, float* out, int32_t waves, int32_t ksplit,
-                               hipStream_t stream)
+                               float* scratch, hipStream_t stream)
 {
     TiledArgs a{};
     a.in = in; a.bias = bias; a.out = out;
     a.slot_channel = t.slot_channel; a.chunk_ptr = t.chunk_ptr; a.steps = t.steps;
     a.w9 = t.w9;
     a.n = s.n; a.c_in = s.c_in; a.c_out = s.c_out; a.h = s.h; a.w = s.w; a.ho = s.ho; a.wo = s.wo;
-    a.pad = s.pad; a.relu = s.relu;
+    a.pad = s.pad; a.relu = s.relu; a.pool = s.pool;
     a.num_groups = t.num_groups;
     a.bx = (s.wo + GEO::TGX * GEO::PC - 1) / (GEO::TGX * GEO::PC);
     a.by = (s.ho + GEO::PR - 1) / GEO::PR;
@@ -412,6 +451,7 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
         hipError_t e = allow_big_lds(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, false>), allowed);
         if (e != hipSuccess) return e;
     }
+    if (s.pool && ksplit > 1 && !scratch) return hipErrorInvalidValue;   // the slices need somewhere to add up
     if (ksplit <= 1) {
         hipLaunchKernelGGL((tiled_conv_kernel<GEO, false>), dim3((unsigned)blocks), dim3(64 * waves), lds_bytes,
                            stream, a);
@@ -429,11 +469,23 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
         }
         const size_t plane = (size_t)s.ho * s.wo, total = (size_t)s.n * s.c_out * plane;
         const unsigned fill_blocks = (unsigned)std::min<size_t>((total + 255) / 256, 256 * 32);
-        hipLaunchKernelGGL(fill_zero_kernel, dim3(fill_blocks), dim3(256), 0, stream, out, total);
+        float* sums = s.pool ? scratch : out;
+        a.out = sums;
+        a.pool = 0;                                  // the slices add plain partial sums
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(fill_blocks), dim3(256), 0, stream, sums, total);
         hipLaunchKernelGGL((tiled_conv_kernel<GEO, true>), dim3((unsigned)blocks, (unsigned)ksplit), dim3(64 * waves),
                            lds_bytes, stream, a);
-        hipLaunchKernelGGL(bias_act_kernel, dim3(fill_blocks), dim3(256), 0, stream, out, bias, s.c_out, plane,
-                           total, s.relu);
+        if (s.pool) {
+            const int pho = s.ho / 2, pwo = s.wo / 2;
+            const size_t ptotal = (size_t)s.n * s.c_out * pho * pwo;
+            const unsigned pblocks = (unsigned)std::min<size_t>((ptotal + 255) / 256, 256 * 32);
+            // max(relu(x + b)) over a window = relu(max(x) + b): one bias add and one ReLU per cell
+            hipLaunchKernelGGL(bias_relu_pool_kernel, dim3(pblocks), dim3(256), 0, stream, sums, bias, out, s.c_out,
+                               s.ho, s.wo, pho, pwo, ptotal);
+        } else {
+            hipLaunchKernelGGL(bias_act_kernel, dim3(fill_blocks), dim3(256), 0, stream, out, bias, s.c_out, plane,
+                               total, s.relu);
+        }
         return hipGetLastError();
     }
 }
@@ -457,6 +509,14 @@ static const TiledVariant kVariants[] = {
     PATDNN_VARIANTS
 #undef X
 };
+
+hipError_t launch_fill_zero(float* p, size_t count, hipStream_t stream)
+{
+    if (count == 0) return hipSuccess;
+    const unsigned blocks = (unsigned)std::min<size_t>((count + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, stream, p, count);
+    return hipGetLastError();
+}
 
 int num_tiled_variants() { return (int)(sizeof(kVariants) / sizeof(kVariants[0])); }
 const TiledVariant& tiled_variant(int i) { return kVariants[i]; }

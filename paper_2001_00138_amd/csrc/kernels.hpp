@@ -12,7 +12,15 @@ namespace patdnn {
 
 struct ConvShape {
     int32_t n, c_in, c_out, h, w, ho, wo, stride, pad, relu;
+    // pool != 0: ReLU, then 2x2 max pooling with stride 2 (floor), fused into the epilogue.
+    // The output tensor is [n][c_out][ho/2][wo/2] and must hold zeros when the kernel
+    // starts: every lane folds its values in with an unsigned integer atomic max on the
+    // float bits, which orders non-negative floats like the floats themselves.
+    int32_t pool = 0;
 };
+
+// Fills `count` floats with zero (a kernel, so that it can be captured into a HIP graph).
+hipError_t launch_fill_zero(float* p, size_t count, hipStream_t stream);
 
 // FKW arrays on the device (paper section 5.3).
 struct DevFkw {
@@ -73,9 +81,11 @@ struct TiledVariant {
     uint32_t table_off;               // offset of block 0 from the code base
     uint32_t ctrl_bytes;              // control block k sits at k*ctrl_bytes
     uint32_t records;                 // kernels per step
-    // ksplit > 1 (sparse variants): slices of the input channels on gridDim.y, summed with atomics
+    // ksplit > 1 (sparse variants): slices of the input channels on gridDim.y, summed with atomics.
+    // With fused pooling the slices are summed in `scratch` ([n][c_out][ho][wo] floats, DEVICE)
+    // and a finishing kernel writes the pooled output; otherwise `scratch` is not used.
     hipError_t (*launch)(const DevTiled&, const ConvShape&, const float*, const float*, float*,
-                         int32_t waves, int32_t ksplit, hipStream_t);
+                         int32_t waves, int32_t ksplit, float* scratch, hipStream_t);
 };
 
 // Device check that s_movrels_b32 / _b64 behave as the threaded interpreter assumes.

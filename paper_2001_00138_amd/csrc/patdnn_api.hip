@@ -211,7 +211,8 @@ patdnn_status_t shape_of(const patdnn_layer* h, int32_t n, int32_t h_in, int32_t
 
 // Launch with an explicit configuration (variant >= 0).
 patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const ConvShape& s,
-                           const float* in, const float* bias, float* out, hipStream_t stream)
+                           const float* in, const float* bias, float* out, hipStream_t stream,
+                           float* scratch = nullptr)
 {
     if (c.variant == PATDNN_VARIANT_FKW) {
         hipError_t e = launch_fkw(h->dfkw, s, in, bias, out, stream);
@@ -241,7 +242,7 @@ patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const Conv
     DevTiled dt = *t;
     if (v.dense) { dt.ck = ck; dt.num_chunks = (s.c_in + ck - 1) / ck; }
     if (c.ksplit > dt.num_chunks) return fail(PATDNN_EUNSUPPORTED, "ksplit exceeds the number of channel chunks");
-    hipError_t e = v.launch(dt, s, in, bias, out, waves, c.ksplit, stream);
+    hipError_t e = v.launch(dt, s, in, bias, out, waves, c.ksplit, scratch, stream);
     return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching a tiled kernel");
 }
 
@@ -337,34 +338,66 @@ patdnn_status_t patdnn_output_shape(patdnn_handle_t h, int32_t n, int32_t h_in, 
     return PATDNN_OK;
 }
 
-patdnn_status_t patdnn_conv2d(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
-                              int32_t w_in, const float* bias, float* output, int32_t fuse_relu,
-                              void* stream)
+// `scratch` (DEVICE, `scratch_floats` floats, may be NULL): where a pooled layer whose
+// configuration splits the input channels adds up its partial sums ([n][c_out][ho][wo]).
+static patdnn_status_t conv2d_impl(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
+                                   int32_t w_in, const float* bias, float* output, int32_t fuse_relu,
+                                   int32_t pool, hipStream_t stream, float* scratch = nullptr,
+                                   size_t scratch_floats = 0)
 {
     ConvShape s{};
     patdnn_status_t st = shape_of(h, n, h_in, w_in, s);
     if (st != PATDNN_OK) return st;
     if (!h->on_device) return fail(PATDNN_EHIP, "handle was encoded with PATDNN_HOST_ONLY");
+    const int oh = pool ? s.ho / 2 : s.ho, ow = pool ? s.wo / 2 : s.wo;
+    if (pool && (oh == 0 || ow == 0)) return fail(PATDNN_EINVAL, "output smaller than one 2x2 pooling window");
+    if (pool && h->L.depthwise) return fail(PATDNN_EUNSUPPORTED, "fused pooling is not built for depthwise layers");
     if (n == 0) return PATDNN_OK;
     if (!input || !output) return fail(PATDNN_EINVAL, "input / output is NULL");
     {
         const char* in_lo = reinterpret_cast<const char*>(input);
         const char* in_hi = in_lo + 4ull * (size_t)n * s.c_in * s.h * s.w;
         const char* out_lo = reinterpret_cast<const char*>(output);
-        const char* out_hi = out_lo + 4ull * (size_t)n * s.c_out * s.ho * s.wo;
+        const char* out_hi = out_lo + 4ull * (size_t)n * s.c_out * oh * ow;
         if (in_lo < out_hi && out_lo < in_hi) return fail(PATDNN_EINVAL, "output overlaps input");
     }
-    s.relu = fuse_relu ? 1 : 0;
+    s.relu = (fuse_relu || pool) ? 1 : 0;
+    s.pool = pool ? 1 : 0;
     patdnn_config_t c = h->cfg;
-    if (c.variant < 0) c = default_config(h, s);
-    st = run_config(h, c, s, input, bias, output, static_cast<hipStream_t>(stream));
+    // a pooled layer that splits the input channels needs room for its partial sums; without
+    // it the layer runs its default configuration
+    const bool split_pool = pool && c.variant > 0 && c.ksplit > 1;
+    const bool have_room = scratch && scratch_floats >= (size_t)n * s.c_out * s.ho * s.wo;
+    if (c.variant < 0 || (split_pool && !have_room)) c = default_config(h, s);
+    if (pool && !(split_pool && have_room)) {
+        hipError_t e = launch_fill_zero(output, (size_t)n * s.c_out * oh * ow, stream);
+        if (e != hipSuccess) return hip_fail(e, "zeroing the pooled output");
+    }
+    st = run_config(h, c, s, input, bias, output, stream, scratch);
     if (st == PATDNN_EUNSUPPORTED && h->cfg.variant > 0 && h->cfg_tuned) {
         // a configuration tuned for another input size may not fit this one; a configuration
         // the caller set explicitly is never replaced: the error goes back instead
         c = default_config(h, s);
-        st = run_config(h, c, s, input, bias, output, static_cast<hipStream_t>(stream));
+        if (pool && split_pool && have_room) {
+            hipError_t e = launch_fill_zero(output, (size_t)n * s.c_out * oh * ow, stream);
+            if (e != hipSuccess) return hip_fail(e, "zeroing the pooled output");
+        }
+        st = run_config(h, c, s, input, bias, output, stream, scratch);
     }
     return st;
+}
+
+patdnn_status_t patdnn_conv2d(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
+                              int32_t w_in, const float* bias, float* output, int32_t fuse_relu,
+                              void* stream)
+{
+    return conv2d_impl(h, input, n, h_in, w_in, bias, output, fuse_relu, 0, static_cast<hipStream_t>(stream));
+}
+
+patdnn_status_t patdnn_conv2d_pool(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
+                                   int32_t w_in, const float* bias, float* output, void* stream)
+{
+    return conv2d_impl(h, input, n, h_in, w_in, bias, output, 1, 1, static_cast<hipStream_t>(stream));
 }
 
 patdnn_status_t patdnn_decode(patdnn_handle_t h, float* dense_weights, uint8_t* pattern_ids,
@@ -557,7 +590,7 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
                 if (w2 > 1 && w2 / 2 >= groups) continue;      // mostly idle wavefronts
                 if (!resolve_tiled_params(h, v, s, ck2, w2)) continue;
                 const int num_chunks = (s.c_in + ck2 - 1) / ck2;
-                for (int ks : {1, 2, 3, 4, 6, 8}) {
+                for (int ks : {1, 2, 3, 4, 6, 8, 12, 16, 24, 32}) {
                     // slices only while the launch before this split leaves wavefront slots empty
                     if (ks > 1 && (v.dense || ks > num_chunks || wavefronts * (ks - 1) >= 2 * kWaveSlots)) continue;
                     patdnn_config_t c{vi + 1, ck2, w2, ks};
@@ -714,6 +747,154 @@ patdnn_status_t patdnn_selftest(void)
 }
 
 void patdnn_destroy(patdnn_handle_t h) { delete h; }
+
+// ---------------------------------------------------------------------------
+// A stack of layers run back to back (section 6.2: one image through all CONV layers)
+// ---------------------------------------------------------------------------
+}  // extern "C"
+
+struct patdnn_stack {
+    std::vector<patdnn_stack_layer_t> layers;
+    int32_t n = 0;
+    std::vector<int32_t> in_h, in_w;          // input size of every layer
+    int32_t out_shape[4] = {0, 0, 0, 0};
+    size_t max_intermediate = 0;              // floats of the largest tensor between two layers
+    size_t buf_floats[2] = {0, 0};            // floats the tensors written to buffer 0 / 1 need
+    size_t split_floats = 0;                  // largest un-pooled output of a pooled layer (partial sums)
+    float* buf[2] = {nullptr, nullptr};       // the stack's own ping-pong buffers
+    float* split = nullptr;                   // and its buffer for the partial sums of split pooled layers
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    const float* graph_in = nullptr;
+    float* graph_out = nullptr;
+    bool warmed = false;                      // one plain run has set every function attribute
+
+    ~patdnn_stack()
+    {
+        if (exec) (void)hipGraphExecDestroy(exec);
+        if (graph) (void)hipGraphDestroy(graph);
+        for (float* p : buf)
+            if (p) (void)hipFree(p);
+        if (split) (void)hipFree(split);
+    }
+};
+
+namespace {
+
+// every layer on `stream`, intermediates alternating between b0 and b1
+patdnn_status_t stack_launch(patdnn_stack* s, const float* input, float* output, float* b0, float* b1,
+                             float* split, hipStream_t stream)
+{
+    const int L = (int)s->layers.size();
+    const float* src = input;
+    for (int i = 0; i < L; ++i) {
+        float* dst = i == L - 1 ? output : ((i & 1) ? b1 : b0);
+        const patdnn_stack_layer_t& ly = s->layers[i];
+        patdnn_status_t st = conv2d_impl(ly.layer, src, s->n, s->in_h[i], s->in_w[i], ly.bias, dst, ly.fuse_relu,
+                                         ly.pool2, stream, split, s->split_floats);
+        if (st != PATDNN_OK) return st;
+        src = dst;
+    }
+    return PATDNN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+patdnn_status_t patdnn_stack_create(const patdnn_stack_layer_t* layers, int32_t num_layers, int32_t n,
+                                    int32_t h_in, int32_t w_in, patdnn_stack_t* out)
+{
+    if (out) *out = nullptr;
+    if (!layers || !out || num_layers <= 0 || n <= 0) return fail(PATDNN_EINVAL, "layers / out is NULL or a size is not positive");
+    std::unique_ptr<patdnn_stack> s(new (std::nothrow) patdnn_stack());
+    if (!s) return fail(PATDNN_ENOMEM, "out of host memory");
+    s->n = n;
+    int32_t h = h_in, w = w_in, c = -1;
+    for (int i = 0; i < num_layers; ++i) {
+        const patdnn_stack_layer_t& ly = layers[i];
+        if (!ly.layer) return fail(PATDNN_EINVAL, "a layer handle is NULL");
+        if (!ly.layer->on_device) return fail(PATDNN_EHIP, "a layer was encoded with PATDNN_HOST_ONLY");
+        if (c >= 0 && ly.layer->L.desc.c_in != c) return fail(PATDNN_EINVAL, "channel counts of consecutive layers do not match");
+        if (ly.pool2 && ly.layer->L.depthwise) return fail(PATDNN_EUNSUPPORTED, "fused pooling is not built for depthwise layers");
+        ConvShape cs{};
+        patdnn_status_t st = shape_of(ly.layer, n, h, w, cs);
+        if (st != PATDNN_OK) return st;
+        s->in_h.push_back(h);
+        s->in_w.push_back(w);
+        h = ly.pool2 ? cs.ho / 2 : cs.ho;
+        w = ly.pool2 ? cs.wo / 2 : cs.wo;
+        if (h <= 0 || w <= 0) return fail(PATDNN_EINVAL, "a layer's output is empty");
+        c = cs.c_out;
+        if (ly.pool2) s->split_floats = std::max(s->split_floats, (size_t)n * c * cs.ho * cs.wo);
+        if (i + 1 < num_layers) {
+            s->max_intermediate = std::max(s->max_intermediate, (size_t)n * c * h * w);
+            s->buf_floats[i & 1] = std::max(s->buf_floats[i & 1], (size_t)n * c * h * w);
+        }
+        s->layers.push_back(ly);
+    }
+    s->out_shape[0] = n; s->out_shape[1] = c; s->out_shape[2] = h; s->out_shape[3] = w;
+    for (int k = 0; k < 2; ++k)
+        if (s->buf_floats[k]) {
+            hipError_t e = hipMalloc(reinterpret_cast<void**>(&s->buf[k]), s->buf_floats[k] * sizeof(float));
+            if (e != hipSuccess) return hip_fail(e, "allocating the stack's intermediate tensors");
+        }
+    if (s->split_floats) {
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&s->split), s->split_floats * sizeof(float));
+        if (e != hipSuccess) return hip_fail(e, "allocating the stack's partial-sum buffer");
+    }
+    *out = s.release();
+    return PATDNN_OK;
+}
+
+patdnn_status_t patdnn_stack_output_shape(patdnn_stack_t s, int32_t out_nchw[4])
+{
+    if (!s || !out_nchw) return fail(PATDNN_EINVAL, "stack / out_nchw is NULL");
+    for (int i = 0; i < 4; ++i) out_nchw[i] = s->out_shape[i];
+    return PATDNN_OK;
+}
+
+patdnn_status_t patdnn_stack_run(patdnn_stack_t s, const float* input, float* output, int32_t use_graph,
+                                 void* stream_)
+{
+    if (!s) return fail(PATDNN_EINVAL, "stack is NULL");
+    if (!input || !output) return fail(PATDNN_EINVAL, "input / output is NULL");
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (!use_graph) {
+        patdnn_status_t st = stack_launch(s, input, output, s->buf[0], s->buf[1], s->split, stream);
+        if (st == PATDNN_OK) s->warmed = true;
+        return st;
+    }
+    if (!stream) return fail(PATDNN_EINVAL, "graph execution needs a stream other than the default one");
+    if (!s->exec || s->graph_in != input || s->graph_out != output) {
+        // (re)capture: the graph holds the tensor addresses it was recorded with
+        if (!s->warmed) {
+            // a first plain run sets the per-kernel attributes, which must not happen in a capture
+            patdnn_status_t st = stack_launch(s, input, output, s->buf[0], s->buf[1], s->split, stream);
+            if (st != PATDNN_OK) return st;
+            s->warmed = true;
+        }
+        if (s->exec) { (void)hipGraphExecDestroy(s->exec); s->exec = nullptr; }
+        if (s->graph) { (void)hipGraphDestroy(s->graph); s->graph = nullptr; }
+        hipError_t e = hipStreamBeginCapture(stream, hipStreamCaptureModeThreadLocal);
+        if (e != hipSuccess) return hip_fail(e, "hipStreamBeginCapture");
+        patdnn_status_t st = stack_launch(s, input, output, s->buf[0], s->buf[1], s->split, stream);
+        e = hipStreamEndCapture(stream, &s->graph);
+        if (st != PATDNN_OK) {
+            if (s->graph) { (void)hipGraphDestroy(s->graph); s->graph = nullptr; }
+            return st;
+        }
+        if (e != hipSuccess) return hip_fail(e, "hipStreamEndCapture");
+        e = hipGraphInstantiate(&s->exec, s->graph, nullptr, nullptr, 0);
+        if (e != hipSuccess) return hip_fail(e, "hipGraphInstantiate");
+        s->graph_in = input;
+        s->graph_out = output;
+    }
+    hipError_t e = hipGraphLaunch(s->exec, stream);
+    return e == hipSuccess ? PATDNN_OK : hip_fail(e, "hipGraphLaunch");
+}
+
+void patdnn_stack_destroy(patdnn_stack_t s) { delete s; }
 
 const char* patdnn_status_string(patdnn_status_t s)
 {

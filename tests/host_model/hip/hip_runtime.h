@@ -86,6 +86,28 @@ inline float unsafeAtomicAdd(float* p, float v)
     return old;
 }
 
+// unsigned atomic max on the output tensor (the fused pooling epilogue folds float bits in)
+inline unsigned atomicMax(unsigned* p, unsigned v)
+{
+    hostmodel::State& st = hostmodel::state();
+    float* fp = reinterpret_cast<float*>(p);
+    if (fp < st.out || fp >= st.out + st.out_floats) {
+        hostmodel::fail("atomic max outside the output tensor", fp - st.out);
+        return 0u;
+    }
+    pthread_mutex_lock(&st.lock);
+    const unsigned old = *p;
+    if (v > old) *p = v;
+    pthread_mutex_unlock(&st.lock);
+    return old;
+}
+inline unsigned __float_as_uint(float f)
+{
+    unsigned u;
+    __builtin_memcpy(&u, &f, 4);
+    return u;
+}
+
 #define __builtin_amdgcn_readfirstlane(x) (x)
 #define __builtin_amdgcn_s_waitcnt(x) ((void)0)
 

@@ -138,7 +138,7 @@ long hostmodel_run(int variant, int G, int num_groups, int ck, int num_chunks, c
     t.G = G; t.num_groups = num_groups; t.ck = ck; t.num_chunks = num_chunks;
     t.slot_channel = slot_channel; t.chunk_ptr = chunk_ptr; t.steps = steps; t.w9 = w9;
     ConvShape s{n, c_in, c_out, h, w, ho, wo, stride, pad, relu};
-    const hipError_t e = tiled_variant(variant).launch(t, s, in, bias, out, waves, ksplit, nullptr);
+    const hipError_t e = tiled_variant(variant).launch(t, s, in, bias, out, waves, ksplit, nullptr, nullptr);
     if (e != hipSuccess) hostmodel::fail("launch refused", e);
     if (msg && msg_len > 0) {
         std::strncpy(msg, st.first_error.c_str(), (size_t)msg_len - 1);
