@@ -480,8 +480,8 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
             const size_t ptotal = (size_t)s.n * s.c_out * pho * pwo;
             const unsigned pblocks = (unsigned)std::min<size_t>((ptotal + 255) / 256, 256 * 32);
             // max(relu(x + b)) over a window = relu(max(x) + b): one bias add and one ReLU per cell
-            hipLaunchKernelGGL(bias_relu_pool_kernel, dim3(pblocks), dim3(256), 0, stream, sums, bias, out, s.c_out,
-                               s.ho, s.wo, pho, pwo, ptotal);
+            hipLaunchKernelGGL(bias_relu_pool_kernel, dim3(pblocks), dim3(256), 0, stream,
+                               static_cast<const float*>(sums), bias, out, s.c_out, s.ho, s.wo, pho, pwo, ptotal);
         } else {
             hipLaunchKernelGGL(bias_act_kernel, dim3(fill_blocks), dim3(256), 0, stream, out, bias, s.c_out, plane,
                                total, s.relu);
