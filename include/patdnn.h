@@ -299,6 +299,22 @@ patdnn_status_t patdnn_stack_output_shape(patdnn_stack_t s, int32_t out_nchw[4])
 patdnn_status_t patdnn_stack_run(patdnn_stack_t s, const float* input, float* output,   /* DEVICE */
                                  int32_t use_graph, void* stream);
 void            patdnn_stack_destroy(patdnn_stack_t s);     /* NULL is a no-op */
+
+/*
+ * patdnn_stack_run (use_graph == 0) for callers that must not allocate or cannot let a
+ * library allocate on their behalf - code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc: the tensors between the layers and the partial sums of
+ * split pooled layers live in a device array built into the library (32 MiB per GPU, held
+ * until the process ends) instead of the stack's own buffers.  The call allocates and frees
+ * nothing.  PATDNN_EUNSUPPORTED (with the two sizes in patdnn_last_error) if the stack needs
+ * more than the array holds: the sum, each rounded up to 256 bytes, of the largest tensor
+ * written by the even-numbered layers, the largest written by the odd-numbered layers (the
+ * last layer writes `output`) and the largest un-pooled output of a pooled layer.  All calls
+ * on one GPU share the array: calls that overlap in time on the same GPU race.  Results are
+ * those of patdnn_stack_run.
+ */
+patdnn_status_t patdnn_stack_run_static(patdnn_stack_t s, const float* input, float* output,   /* DEVICE */
+                                        void* stream);
 const char* patdnn_status_string(patdnn_status_t s);
 const char* patdnn_last_error(void);
 

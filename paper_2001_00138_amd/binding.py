@@ -23,7 +23,7 @@ PATDNN_VARIANT_FKW = 0
 
 EXPORTS = [
     "patdnn_encode", "patdnn_conv2d", "patdnn_conv2d_pool", "patdnn_output_shape", "patdnn_decode",
-    "patdnn_stack_create", "patdnn_stack_output_shape", "patdnn_stack_run", "patdnn_stack_destroy",
+    "patdnn_stack_create", "patdnn_stack_output_shape", "patdnn_stack_run", "patdnn_stack_run_static", "patdnn_stack_destroy",
     "patdnn_export_fkw", "patdnn_layout_stats", "patdnn_num_variants", "patdnn_variant_name",
     "patdnn_set_config", "patdnn_get_config", "patdnn_tune", "patdnn_tiled_info",
     "patdnn_export_tiled", "patdnn_selftest", "patdnn_destroy",
@@ -94,6 +94,7 @@ def lib() -> ctypes.CDLL:
         L.patdnn_stack_create.argtypes = [ctypes.POINTER(StackLayer), i32, i32, i32, i32, ctypes.POINTER(vp)]
         L.patdnn_stack_output_shape.argtypes = [vp, ctypes.POINTER(i32 * 4)]
         L.patdnn_stack_run.argtypes = [vp, vp, vp, i32, vp]
+        L.patdnn_stack_run_static.argtypes = [vp, vp, vp, vp]
         L.patdnn_stack_destroy.argtypes = [vp]
         L.patdnn_stack_destroy.restype = None
         L.patdnn_output_shape.argtypes = [vp, i32, i32, i32, ctypes.POINTER(i32 * 4)]
@@ -244,6 +245,11 @@ class Stack:
             out = torch.empty(self.output_shape(), dtype=torch.float32, device=x.device)
         _check(lib().patdnn_stack_run(self.handle, _devptr(x), _devptr(out), int(bool(graph)),
                                       _stream_ptr(stream)))
+        return out
+
+    def run_static(self, x, out, *, stream=None):
+        """patdnn_stack_run_static: the library's built-in buffer instead of the stack's own."""
+        _check(lib().patdnn_stack_run_static(self.handle, _devptr(x), _devptr(out), _stream_ptr(stream)))
         return out
 
     def close(self):

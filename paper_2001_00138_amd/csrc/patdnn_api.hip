@@ -9,6 +9,7 @@
 #include <iterator>
 #include <map>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <utility>
@@ -895,6 +896,69 @@ patdnn_status_t patdnn_stack_run(patdnn_stack_t s, const float* input, float* ou
 }
 
 void patdnn_stack_destroy(patdnn_stack_t s) { delete s; }
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------
+// patdnn_stack_run without any allocation behind it: the tensors between the layers and the
+// partial sums of split pooled layers live in one file-scope device array instead of the
+// stack's own buffers.  Every GPU the library runs on holds its own copy of the array until
+// the process ends; calls that overlap on one GPU share it and race.
+// ---------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kStaticScratchBytes = 32u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];              // device address of `scratch`, per device
+std::mutex g_scratch_lock;
+
+// The array's device address on the current device (looked up once per device; in host code
+// the array's name is only a handle for this lookup, never an address to pass to a kernel).
+hipError_t static_scratch(unsigned char** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<unsigned char*>(g_scratch_ptr[dev]);
+    return hipSuccess;
+}
+
+size_t round256(size_t bytes) { return (bytes + 255) / 256 * 256; }
+
+}  // namespace
+
+extern "C" {
+
+patdnn_status_t patdnn_stack_run_static(patdnn_stack_t s, const float* input, float* output, void* stream)
+{
+    if (!s) return fail(PATDNN_EINVAL, "stack is NULL");
+    if (!input || !output) return fail(PATDNN_EINVAL, "input / output is NULL");
+    const size_t b0 = round256(s->buf_floats[0] * sizeof(float)), b1 = round256(s->buf_floats[1] * sizeof(float));
+    const size_t sp = round256(s->split_floats * sizeof(float));
+    if (b0 + b1 + sp > kStaticScratchBytes) {
+        char msg[200];
+        snprintf(msg, sizeof(msg), "the stack needs %zu bytes between its layers; the built-in buffer of "
+                 "patdnn_stack_run_static holds %zu", b0 + b1 + sp, kStaticScratchBytes);
+        return fail(PATDNN_EUNSUPPORTED, msg);
+    }
+    unsigned char* base = nullptr;
+    hipError_t e = static_scratch(&base);
+    if (e != hipSuccess) return hip_fail(e, "looking up the built-in buffer");
+    // nothing here needs to start at zero: the kernels clear the pooled outputs and partial
+    // sums they accumulate into, whatever an earlier call left behind
+    return stack_launch(s, input, output, reinterpret_cast<float*>(base), reinterpret_cast<float*>(base + b0),
+                        reinterpret_cast<float*>(base + b0 + b1), static_cast<hipStream_t>(stream));
+}
 
 const char* patdnn_status_string(patdnn_status_t s)
 {
