@@ -61,6 +61,10 @@ def main() -> int:
     ap.add_argument("--no-other-stacks", action="store_true",
                     help="skip the per-layer rows of the ResNet-50 / MobileNet-V2 shaped stacks")
     ap.add_argument("--no-peaks", action="store_true", help="skip the stream-copy and FMA-loop probes")
+    ap.add_argument("--no-ablation", action="store_true",
+                    help="skip the per-layer breakdown (No-opt / +reorder / +LRE / +tuning, CSR, dense)")
+    ap.add_argument("--no-pattern-sweep", action="store_true",
+                    help="skip the timing of one layer with pattern sets of 6 / 8 / 12 / 56 patterns")
     ap.add_argument("--only-timed", action="store_true",
                     help="the timed region only (for profiler runs): implies every --no-* leg above")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -77,7 +81,7 @@ def main() -> int:
         return 2
     if args.only_timed:
         args.no_cpu_baseline = args.no_dense_compare = args.no_latency = True
-        args.no_other_stacks = args.no_peaks = True
+        args.no_other_stacks = args.no_peaks = args.no_ablation = args.no_pattern_sweep = True
 
     import numpy as np
     import torch
@@ -401,6 +405,71 @@ def main() -> int:
             Ld.close()
         dense_cmp = rows
 
+    # ------------------------------------------------------------------ per-layer breakdown (section 6.3)
+    # No-opt -> +filter-kernel reorder -> +load-redundancy elimination -> +tuning on the unique
+    # layer shapes of the stack, with the CSR control (section 6.2) and the dense kernel beside it
+    ablation = None
+    if not args.no_ablation and args.config == 5:
+        names_ = {B.patdnn_variant_name(v): v for v in range(B.patdnn_num_variants())}
+        rows, seen_shapes = [], set()
+        for k, ly in enumerate(layers):
+            spec = ly["spec"]
+            if spec.dense or spec.depthwise or wl.shape_key(spec) in seen_shapes:
+                continue
+            seen_shapes.add(wl.shape_key(spec))
+            L = ly["L"]
+            tuned_cfg = L.get_config()
+            run = lambda: L.conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+            ms = {}
+            for stage, (vname, ck, waves) in (("noopt", ("noopt", 0, 0)), ("reorder", ("fkw", 0, 0)),
+                                              ("lre", ("t_g16_p7x1_s1_x16", 0, 0)), ("csr", ("csr", 0, 0))):
+                L.set_config(names_[vname], ck, waves, 1)
+                run()
+                ms[stage] = sorted(timed_ms(run, 3))[1]
+            L.set_config(tuned_cfg["variant"], tuned_cfg["ck"], tuned_cfg["waves"], tuned_cfg["ksplit"])
+            run()
+            ms["tuned"] = sorted(timed_ms(run, 5))[2]
+            Ld = B.Layer(ly["d"]["weights"], None, None, None, stride=spec.stride, pad=spec.pad, dense=True)
+            rund = lambda: Ld.conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+            rund()
+            ms["dense"] = sorted(timed_ms(rund, 3))[1]
+            Ld.close()
+            rows.append({"layer": spec.name, "shape": f"{spec.c_in}->{spec.c_out}@{spec.h}", "n": spec.n,
+                         "ms": {kk: round(v, 4) for kk, v in ms.items()},
+                         "speedup_reorder": round(ms["noopt"] / ms["reorder"], 2),
+                         "speedup_lre": round(ms["reorder"] / ms["lre"], 2),
+                         "speedup_tuning": round(ms["lre"] / ms["tuned"], 2),
+                         "csr_over_dense": round(ms["csr"] / ms["dense"], 2),
+                         "dense_over_pattern": round(ms["dense"] / ms["tuned"], 2)})
+        ablation = {"note": "noopt: one lane per pixel, original filter / kernel order, pattern decided per "
+                            "kernel in the inner loop; reorder: the same lane mapping over the FKW arrays; lre: "
+                            "the tiled kernel in its default configuration; tuned: the autotuner's choice; csr: "
+                            "one lane per pixel over CSR; dense: the dense direct kernel on unpruned weights",
+                    "layers": rows}
+
+    # ------------------------------------------------------------------ pattern-count sweep (section 6.6)
+    # the same layer with libraries of 6 / 8 / 12 / 56 patterns: the kernels carry a code body for
+    # every one of the 56 centre-keeping patterns, so the set size only changes the streams
+    sweep = None
+    if not args.no_pattern_sweep and args.config == 5:
+        sweep = {"note": "128->128@112 and 512->512@28 at N=64, keep 1/3.6, pattern ids uniform over a seeded "
+                         "library of k patterns; same launch configuration as the 8-pattern layer", "rows": []}
+        for li in (3, 8):
+            ly = layers[li]
+            spec, d = ly["spec"], ly["d"]
+            cfg0 = ly["L"].get_config()
+            for kpat in (6, 8, 12, 56):
+                lib_k = wl.pattern_library(wl.PATTERN_SEED, kpat)
+                ids_k = np.random.default_rng(600 + kpat).integers(0, kpat, d["pattern_ids"].shape, dtype=np.uint8)
+                Lk = B.Layer(d["weights"], ids_k, d["kernel_mask"], lib_k, stride=spec.stride, pad=spec.pad)
+                Lk.set_config(cfg0["variant"], cfg0["ck"], cfg0["waves"], cfg0["ksplit"])
+                runk = lambda: Lk.conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+                runk()
+                ms = sorted(timed_ms(runk, 7))[3]
+                sweep["rows"].append({"layer": spec.name, "patterns": kpat, "ms": round(ms, 4),
+                                      "nz_gflops": round(ly["nz"] / (ms * 1e-3) / 1e9, 1)})
+                Lk.close()
+
     # ------------------------------------------------------------------ CPU oracle beside it
     cpu = None
     if not args.no_cpu_baseline:
@@ -444,6 +513,8 @@ def main() -> int:
         "layers": layer_rows,
         "other_stacks": other,
         "dense_compare": dense_cmp,
+        "ablation": ablation,
+        "pattern_count_sweep": sweep,
     }
     print(json.dumps(result), flush=True)
     return 0

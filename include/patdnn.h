@@ -136,6 +136,17 @@ patdnn_status_t patdnn_decode(patdnn_handle_t h, float* dense_weights, uint8_t* 
 patdnn_status_t patdnn_export_fkw(patdnn_handle_t h, int32_t* offset, int32_t* reorder,
                                   int32_t* index, int32_t* stride, float* weight);
 
+/*
+ * The layer as the conventional compressed-sparse-row matrix A[c_out][c_in*9] that the paper
+ * compares its storage with (section 5.3, section 6.3) and that the "csr" kernel reads:
+ * column = ci*9 + 3*kh + kw, the kept positions of every surviving kernel, ascending per
+ * filter, filters in their original order.  `*nnz` receives the number of stored weights
+ * (4 x kept kernels); row_ptr [c_out+1], col [nnz], val [nnz] are HOST buffers, any may be
+ * NULL (call once with only `nnz` to size them).  Pruned, non-depthwise layers.
+ */
+patdnn_status_t patdnn_export_csr(patdnn_handle_t h, int64_t* nnz, int32_t* row_ptr, int32_t* col,
+                                  float* val);
+
 typedef struct {
     int64_t kept_kernels;      /* kernels that survived connectivity pruning */
     int32_t taps;              /* stored weights per kernel: 4, or 9 for a dense layer */
@@ -163,6 +174,12 @@ patdnn_status_t patdnn_layout_stats(patdnn_handle_t h, patdnn_stats_t* out);
  *   after the tiled ones    "dw_p1x4": depthwise layers (groups == c_in), one pass over
  *                           input and output with 16-byte accesses, four outputs per lane;
  *                           the default for such layers (section 6.1 evaluates MobileNet-V2)
+ *                           "noopt", "csr": comparison kernels of the paper's evaluation, never
+ *                           chosen by the library: the layer before filter-kernel reorder with
+ *                           the pattern of every kernel decided inside the inner loop (the
+ *                           "No-opt" stage of the per-layer breakdown, section 6.3), and the
+ *                           layer as a CSR matrix (the control of section 6.2); pruned,
+ *                           non-depthwise layers only
  * A configuration set with patdnn_set_config is taken as given or refused
  * (PATDNN_EUNSUPPORTED), never replaced by another one at launch time.
  * `ck` = input channels staged per LDS pass, `waves` = wavefronts (filter groups)

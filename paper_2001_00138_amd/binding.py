@@ -24,7 +24,7 @@ PATDNN_VARIANT_FKW = 0
 EXPORTS = [
     "patdnn_encode", "patdnn_conv2d", "patdnn_conv2d_pool", "patdnn_output_shape", "patdnn_decode",
     "patdnn_stack_create", "patdnn_stack_output_shape", "patdnn_stack_run", "patdnn_stack_run_static", "patdnn_stack_destroy",
-    "patdnn_export_fkw", "patdnn_layout_stats", "patdnn_num_variants", "patdnn_variant_name",
+    "patdnn_export_fkw", "patdnn_export_csr", "patdnn_layout_stats", "patdnn_num_variants", "patdnn_variant_name",
     "patdnn_set_config", "patdnn_get_config", "patdnn_tune", "patdnn_tiled_info",
     "patdnn_export_tiled", "patdnn_selftest", "patdnn_destroy",
     "patdnn_status_string", "patdnn_last_error",
@@ -101,6 +101,7 @@ def lib() -> ctypes.CDLL:
         L.patdnn_decode.argtypes = [vp, vp, vp, vp]
         L.patdnn_export_fkw.argtypes = [vp, vp, vp, vp, vp, vp]
         L.patdnn_layout_stats.argtypes = [vp, ctypes.POINTER(Stats)]
+        L.patdnn_export_csr.argtypes = [vp, ctypes.POINTER(ctypes.c_int64), vp, vp, vp]
         L.patdnn_num_variants.argtypes = []
         L.patdnn_variant_name.argtypes = [i32]
         L.patdnn_variant_name.restype = ctypes.c_char_p
@@ -289,6 +290,16 @@ def patdnn_export_fkw(handle: int, c_out: int) -> dict:
     return out
 
 
+def patdnn_export_csr(handle: int, c_out: int) -> dict:
+    nnz = ctypes.c_int64()
+    _check(lib().patdnn_export_csr(handle, ctypes.byref(nnz), None, None, None))
+    out = {"row_ptr": np.empty(c_out + 1, np.int32), "col": np.empty(nnz.value, np.int32),
+           "val": np.empty(nnz.value, np.float32)}
+    _check(lib().patdnn_export_csr(handle, None, out["row_ptr"].ctypes.data, out["col"].ctypes.data,
+                                   out["val"].ctypes.data))
+    return out
+
+
 def patdnn_num_variants() -> int:
     return int(lib().patdnn_num_variants())
 
@@ -381,6 +392,9 @@ class Layer:
 
     def export_fkw(self):
         return patdnn_export_fkw(self.handle, self.c_out)
+
+    def export_csr(self):
+        return patdnn_export_csr(self.handle, self.c_out)
 
     def stats(self):
         return patdnn_layout_stats(self.handle)

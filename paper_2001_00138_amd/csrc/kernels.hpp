@@ -54,6 +54,17 @@ struct DevTiled {
 hipError_t launch_fkw(const DevFkw& f, const ConvShape& s, const float* in, const float* bias,
                       float* out, hipStream_t stream);
 
+// The comparison kernels' views of a layer (kernel_compare.hip): the layer before
+// filter-kernel reorder, and as a CSR matrix.
+struct DevCompare {
+    const int32_t* row_ptr = nullptr;
+    const int32_t* col = nullptr;
+    const int32_t* kmask = nullptr;
+    const float* val = nullptr;
+};
+hipError_t launch_compare(bool csr, const DevCompare& d, const ConvShape& s, const float* in, const float* bias,
+                          float* out, hipStream_t stream);
+
 // Depthwise layers: one pass over input and output, 16-byte accesses, four outputs per lane.
 hipError_t launch_dw(const DevFkw& f, const ConvShape& s, const float* in, const float* bias,
                      float* out, hipStream_t stream);

@@ -56,6 +56,13 @@ struct patdnn_layer {
     // by (variant index, ck); dense variants use ck = 0
     std::map<std::pair<int, int>, std::unique_ptr<TiledOnDevice>> tiled;
     std::vector<void*> allocations;
+    // the comparison kernels' layouts (built when such a variant is first selected)
+    struct CompareHost {
+        std::vector<int32_t> row_ptr, col, kmask;
+        std::vector<float> val;
+    } noopt_host, csr_host;
+    DevCompare noopt_dev, csr_dev;
+    bool compare_built = false, compare_on_device = false;
     patdnn_config_t cfg{-1, 0, 0, 1};                      // variant -1: choose per call
     bool cfg_tuned = false;                                // cfg came from patdnn_tune (for one input size)
 
@@ -115,10 +122,10 @@ bool variant_selectable(const patdnn_layer* h, const TiledVariant& v)
 }
 
 // Variant numbers: 0 the FKW walk, 1..T the tiled variants, then the kernels below.
-enum ExtraVariant { kExtraDepthwise = 0, kNumExtra };
+enum ExtraVariant { kExtraDepthwise = 0, kExtraNoopt, kExtraCsr, kNumExtra };
 int extra_variant(int variant) { return variant - 1 - num_tiled_variants(); }     // < 0: not one
 int variant_of_extra(int extra) { return 1 + num_tiled_variants() + extra; }
-const char* const kExtraNames[kNumExtra] = {"dw_p1x4"};
+const char* const kExtraNames[kNumExtra] = {"dw_p1x4", "noopt", "csr"};
 
 constexpr int kMaxLdsBytes = 160 * 1024;      // LDS of one CU; two staging buffers must fit
 constexpr int kMaxWaves = 8;
@@ -193,6 +200,62 @@ patdnn_status_t ensure_tiled(patdnn_layer* h, int vi, int ck, const DevTiled** o
     return PATDNN_OK;
 }
 
+// The layer before filter-kernel reorder (filters in original order, kernels by input
+// channel, a pattern mask per kernel) and as a CSR matrix [c_out][c_in*9], both derived from
+// the FKW arrays by undoing the reorder.
+patdnn_status_t ensure_compare(patdnn_layer* h)
+{
+    if (h->L.depthwise || h->L.dense) return fail(PATDNN_EUNSUPPORTED, "the comparison kernels run pruned, non-depthwise layers");
+    if (!h->compare_built) {
+        const Fkw& f = h->L.fkw;
+        const int c_out = h->L.desc.c_out, P = f.num_patterns;
+        struct K { int32_t ci; int32_t mask; const float* w; };
+        std::vector<std::vector<K>> per_filter((size_t)c_out);
+        for (int s = 0; s < c_out; ++s) {
+            const int32_t* st = &f.stride[(size_t)s * (P + 1)];
+            for (int p = 0; p < P; ++p)
+                for (int32_t k = f.offset[s] + st[p]; k < f.offset[s] + st[p + 1]; ++k)
+                    per_filter[(size_t)f.reorder[s]].push_back(K{f.index[k], (int32_t)f.masks[p], &f.weight[(size_t)k * 4]});
+        }
+        auto& no = h->noopt_host;
+        auto& cs = h->csr_host;
+        no.row_ptr.assign(1, 0);
+        cs.row_ptr.assign(1, 0);
+        for (int co = 0; co < c_out; ++co) {
+            auto& ks = per_filter[(size_t)co];
+            std::sort(ks.begin(), ks.end(), [](const K& a, const K& b) { return a.ci < b.ci; });
+            for (const K& k : ks) {
+                no.col.push_back(k.ci);
+                no.kmask.push_back(k.mask);
+                int t = 0;
+                for (int pos = 0; pos < 9; ++pos)
+                    if ((k.mask >> pos) & 1) {
+                        no.val.push_back(k.w[t]);
+                        cs.col.push_back(k.ci * 9 + pos);
+                        cs.val.push_back(k.w[t]);
+                        ++t;
+                    }
+            }
+            no.row_ptr.push_back((int32_t)no.col.size());
+            cs.row_ptr.push_back((int32_t)cs.col.size());
+        }
+        h->compare_built = true;
+    }
+    if (h->on_device && !h->compare_on_device) {
+        hipError_t e;
+        if ((e = upload(h->allocations, h->noopt_host.row_ptr, &h->noopt_dev.row_ptr)) != hipSuccess ||
+            (e = upload(h->allocations, h->noopt_host.col, &h->noopt_dev.col)) != hipSuccess ||
+            (e = upload(h->allocations, h->noopt_host.kmask, &h->noopt_dev.kmask)) != hipSuccess ||
+            (e = upload(h->allocations, h->noopt_host.val, &h->noopt_dev.val)) != hipSuccess ||
+            (e = upload(h->allocations, h->csr_host.row_ptr, &h->csr_dev.row_ptr)) != hipSuccess ||
+            (e = upload(h->allocations, h->csr_host.col, &h->csr_dev.col)) != hipSuccess ||
+            (e = upload(h->allocations, h->csr_host.val, &h->csr_dev.val)) != hipSuccess)
+            return hip_fail(e, "uploading the comparison layouts");
+        h->compare_on_device = true;
+    }
+    return PATDNN_OK;
+}
+
 patdnn_status_t shape_of(const patdnn_layer* h, int32_t n, int32_t h_in, int32_t w_in, ConvShape& s)
 {
     if (!h) return fail(PATDNN_EINVAL, "handle is NULL");
@@ -223,6 +286,13 @@ patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const Conv
         if (!h->L.depthwise) return fail(PATDNN_EUNSUPPORTED, "the depthwise kernel runs depthwise layers only");
         hipError_t e = launch_dw(h->dfkw, s, in, bias, out, stream);
         return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching the depthwise kernel");
+    }
+    if (extra_variant(c.variant) == kExtraNoopt || extra_variant(c.variant) == kExtraCsr) {
+        if (!h->compare_on_device) return fail(PATDNN_EUNSUPPORTED, "select the comparison kernel with patdnn_set_config first");
+        if (s.pool) return fail(PATDNN_EUNSUPPORTED, "the comparison kernels have no pooled epilogue");
+        const bool csr = extra_variant(c.variant) == kExtraCsr;
+        hipError_t e = launch_compare(csr, csr ? h->csr_dev : h->noopt_dev, s, in, bias, out, stream);
+        return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching a comparison kernel");
     }
     const int vi = c.variant - 1;
     if (vi < 0 || vi >= num_tiled_variants()) return fail(PATDNN_EINVAL, "no such variant");
@@ -460,6 +530,31 @@ patdnn_status_t patdnn_export_fkw(patdnn_handle_t h, int32_t* offset, int32_t* r
     return PATDNN_OK;
 }
 
+patdnn_status_t patdnn_export_csr(patdnn_handle_t h, int64_t* nnz, int32_t* row_ptr, int32_t* col, float* val)
+{
+    if (!h) return fail(PATDNN_EINVAL, "handle is NULL");
+    try {
+        patdnn_status_t st = ensure_compare(h);
+        if (st != PATDNN_OK) return st;
+    } catch (const std::bad_alloc&) {
+        return fail(PATDNN_ENOMEM, "out of host memory");
+    }
+    const auto& c = h->csr_host;
+    if (nnz) *nnz = (int64_t)c.col.size();
+    auto get = [&](void* dst, const void* dev, const void* host, size_t bytes) -> hipError_t {
+        if (!dst || !bytes) return hipSuccess;
+        if (h->on_device) return hipMemcpy(dst, dev, bytes, hipMemcpyDeviceToHost);
+        std::memcpy(dst, host, bytes);
+        return hipSuccess;
+    };
+    hipError_t e;
+    if ((e = get(row_ptr, h->csr_dev.row_ptr, c.row_ptr.data(), c.row_ptr.size() * 4)) != hipSuccess ||
+        (e = get(col, h->csr_dev.col, c.col.data(), c.col.size() * 4)) != hipSuccess ||
+        (e = get(val, h->csr_dev.val, c.val.data(), c.val.size() * 4)) != hipSuccess)
+        return hip_fail(e, "reading the CSR arrays back");
+    return PATDNN_OK;
+}
+
 patdnn_status_t patdnn_layout_stats(patdnn_handle_t h, patdnn_stats_t* out)
 {
     if (!h || !out) return fail(PATDNN_EINVAL, "handle / out is NULL");
@@ -512,6 +607,17 @@ patdnn_status_t patdnn_set_config(patdnn_handle_t h, const patdnn_config_t* cfg)
     if (cfg->variant >= patdnn_num_variants()) return fail(PATDNN_EINVAL, "no such variant");
     if (extra_variant(cfg->variant) == kExtraDepthwise) {
         if (!h->L.depthwise) return fail(PATDNN_EUNSUPPORTED, "the depthwise kernel runs depthwise layers only");
+        h->cfg = patdnn_config_t{cfg->variant, 0, 0, 1};
+        h->cfg_tuned = false;
+        return PATDNN_OK;
+    }
+    if (extra_variant(cfg->variant) == kExtraNoopt || extra_variant(cfg->variant) == kExtraCsr) {
+        try {
+            patdnn_status_t st = ensure_compare(h);
+            if (st != PATDNN_OK) return st;
+        } catch (const std::bad_alloc&) {
+            return fail(PATDNN_ENOMEM, "out of host memory");
+        }
         h->cfg = patdnn_config_t{cfg->variant, 0, 0, 1};
         h->cfg_tuned = false;
         return PATDNN_OK;

@@ -82,3 +82,31 @@ def test_every_variant_and_ksplit_matches_the_oracle(torch, oracle, case):
     finally:
         L.close()
     assert seen > 0
+
+
+@pytest.mark.parametrize("kpat", [6, 12, 56])
+def test_pattern_sets_of_other_sizes(torch, oracle, kpat):
+    """Libraries of 6, 12 and all 56 patterns (the paper's study of the pattern count,
+    section 6.6) on a 128 -> 128 layer at the paper's density, in the configuration the
+    benchmark's sweep uses for that shape and in the library default."""
+    import os
+    rng = np.random.default_rng(6600 + kpat)
+    lib = wl.pattern_library(wl.PATTERN_SEED, kpat)
+    c = 128
+    ids = rng.integers(0, kpat, (c, c), dtype=np.uint8)
+    mask = (rng.random((c, c)) < 1 / 3.6).astype(np.uint8)
+    w = (rng.standard_normal((c, c, 3, 3)) * np.sqrt(2 / (9 * c))).astype(np.float32)
+    bias = (rng.standard_normal(c) * 0.01).astype(np.float32)
+    x = np.maximum(rng.standard_normal((4, c, 56, 56)), 0).astype(np.float32)
+    ref = oracle.conv2d(w, ids, mask, lib, x, bias, relu=True, skip_removed=True)
+    L = B.Layer(w, ids, mask, lib)
+    names = {B.patdnn_variant_name(v): v for v in range(B.patdnn_num_variants())}
+    xt, bt = torch.from_numpy(x).cuda(), torch.from_numpy(bias).cuda()
+    for cfg in (None, ("t_g8_p7x2_s1_x8_thw1b", 8, 4, 1), ("t_g12_p7x1_s1_x16_th", 8, 4, 2)):
+        if cfg is not None:
+            L.set_config(names[cfg[0]], *cfg[1:])
+        got = L.conv2d(xt, bt, relu=True).cpu().numpy()
+        err = float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
+        _say(f"    {kpat} patterns cfg={cfg}: rel_err={err:.2e}")
+        assert err <= TOL
+    L.close()

@@ -403,3 +403,25 @@ def test_an_explicit_configuration_is_strict():
     assert e.value.status == B.PATDNN_EUNSUPPORTED
     assert L.get_config()["ksplit"] == 2           # the refused configuration replaced nothing
     L.close()
+
+
+@pytest.mark.parametrize("config,layer", [(1, 0), (2, 3), (3, 3)])
+def test_exported_csr_is_the_textbook_csr_of_the_pruned_layer(config, layer):
+    """The CSR arrays the comparison kernel reads, against the oracle's CSR (itself pinned to
+    scipy's): same row pointers, columns and weight bits."""
+    from oracle import csr as ocsr
+    d = wl.gen_layer(config, layer, with_input=False)
+    L = _host_layer(d)
+    got = L.export_csr()
+    row_ptr, col, val = ocsr.build_csr(d["weights"], d["pattern_ids"], d["kernel_mask"], d["pattern_masks"])
+    np.testing.assert_array_equal(got["row_ptr"], row_ptr)
+    np.testing.assert_array_equal(got["col"], col)
+    assert got["val"].view(np.uint32).tolist() == val.view(np.uint32).tolist()
+    L.close()
+    # dense and depthwise layers have no such form here
+    for cfg, li in ((2, 0), (4, 0)):
+        Ld = _host_layer(wl.gen_layer(cfg, li, with_input=False))
+        with pytest.raises(B.PatdnnError) as e:
+            Ld.export_csr()
+        assert e.value.status == B.PATDNN_EUNSUPPORTED
+        Ld.close()
