@@ -82,6 +82,31 @@ patdnn_status_t patdnn_encode(const patdnn_layer_desc_t* desc, const float* dens
                               patdnn_handle_t* out);
 
 /*
+ * The projection operators of the pattern-based pruning stage (section 4.1, 4.2), as host
+ * utilities that turn any dense weight tensor into the arrays patdnn_encode takes.  All
+ * pointers HOST; weights [c_out][kernels_per_filter][3][3] fp32.  Magnitudes and norms are
+ * compared in double computed from the fp32 values, summed over positions 0..8 in order.
+ *   patdnn_mine_patterns       the natural pattern of a kernel is its centre plus the three
+ *       other positions of largest magnitude (equal magnitudes: lower position); the k most
+ *       frequent natural patterns over all kernels, most frequent first (equal counts: lower
+ *       mask), are written to pattern_masks [k]; *found = how many there are (<= k).
+ *   patdnn_project_patterns    per kernel, the pattern of the set that retains the largest
+ *       sum of squares (equal: lower id) - the Euclidean projection onto the pattern
+ *       constraint; writes pattern_ids [c_out][kernels_per_filter] and, if `projected` is not
+ *       NULL, the projected weights (positions outside the chosen pattern zeroed).
+ *   patdnn_project_connectivity  kernel_mask = 1 for the min(alpha, all) kernels of largest
+ *       L2 norm (equal norms: lower index co*kernels_per_filter + ci), 0 for the others - the
+ *       Euclidean projection onto the connectivity constraint.
+ */
+patdnn_status_t patdnn_mine_patterns(const float* dense_weights, int32_t c_out, int32_t kernels_per_filter,
+                                     int32_t k, uint16_t* pattern_masks, int32_t* found);
+patdnn_status_t patdnn_project_patterns(const float* dense_weights, int32_t c_out, int32_t kernels_per_filter,
+                                        const uint16_t* pattern_masks, int32_t num_patterns,
+                                        uint8_t* pattern_ids, float* projected);
+patdnn_status_t patdnn_project_connectivity(const float* dense_weights, int32_t c_out, int32_t kernels_per_filter,
+                                            int64_t alpha, uint8_t* kernel_mask);
+
+/*
  * The layer itself (section 2.1 CONV + ReLU; executed from the reordered layout as
  * in section 5.2-5.4).  Asynchronous on `stream`; allocates nothing, never
  * synchronises.

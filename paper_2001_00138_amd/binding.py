@@ -22,6 +22,7 @@ PATDNN_DENSE, PATDNN_STRICT, PATDNN_HOST_ONLY = 1, 2, 4
 PATDNN_VARIANT_FKW = 0
 
 EXPORTS = [
+    "patdnn_mine_patterns", "patdnn_project_patterns", "patdnn_project_connectivity",
     "patdnn_encode", "patdnn_conv2d", "patdnn_conv2d_pool", "patdnn_output_shape", "patdnn_decode",
     "patdnn_stack_create", "patdnn_stack_output_shape", "patdnn_stack_run", "patdnn_stack_run_static", "patdnn_stack_destroy",
     "patdnn_export_fkw", "patdnn_export_csr", "patdnn_layout_stats", "patdnn_num_variants", "patdnn_variant_name",
@@ -90,6 +91,9 @@ def lib() -> ctypes.CDLL:
         vp, i32 = ctypes.c_void_p, ctypes.c_int32
         L.patdnn_encode.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, vp, ctypes.POINTER(vp)]
         L.patdnn_conv2d.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp]
+        L.patdnn_mine_patterns.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(i32)]
+        L.patdnn_project_patterns.argtypes = [vp, i32, i32, vp, i32, vp, vp]
+        L.patdnn_project_connectivity.argtypes = [vp, i32, i32, ctypes.c_int64, vp]
         L.patdnn_conv2d_pool.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
         L.patdnn_stack_create.argtypes = [ctypes.POINTER(StackLayer), i32, i32, i32, i32, ctypes.POINTER(vp)]
         L.patdnn_stack_output_shape.argtypes = [vp, ctypes.POINTER(i32 * 4)]
@@ -161,6 +165,34 @@ def _stream_ptr(stream) -> Optional[int]:
 # ---------------------------------------------------------------------------
 # functions named after the C entry points
 # ---------------------------------------------------------------------------
+
+def patdnn_mine_patterns(dense_weights, k: int) -> np.ndarray:
+    """The k most frequent natural patterns of [c_out][kpf][3][3] weights (uint16 masks)."""
+    w, wp = _host(dense_weights, np.float32)
+    masks = np.zeros(k, np.uint16)
+    found = ctypes.c_int32()
+    _check(lib().patdnn_mine_patterns(wp, w.shape[0], w.shape[1], k, masks.ctypes.data, ctypes.byref(found)))
+    return masks[:found.value]
+
+
+def patdnn_project_patterns(dense_weights, pattern_masks):
+    """-> (pattern_ids uint8 [c_out][kpf], projected fp32 weights)"""
+    w, wp = _host(dense_weights, np.float32)
+    pm, pp = _host(pattern_masks, np.uint16)
+    ids = np.zeros(w.shape[:2], np.uint8)
+    proj = np.empty_like(w)
+    _check(lib().patdnn_project_patterns(wp, w.shape[0], w.shape[1], pp, len(pm), ids.ctypes.data,
+                                         proj.ctypes.data))
+    return ids, proj
+
+
+def patdnn_project_connectivity(dense_weights, alpha: int) -> np.ndarray:
+    """-> kernel_mask uint8 [c_out][kpf] keeping the alpha kernels of largest L2 norm"""
+    w, wp = _host(dense_weights, np.float32)
+    mask = np.zeros(w.shape[:2], np.uint8)
+    _check(lib().patdnn_project_connectivity(wp, w.shape[0], w.shape[1], int(alpha), mask.ctypes.data))
+    return mask
+
 
 def patdnn_encode(dense_weights, pattern_ids, kernel_mask, pattern_masks, *, stride=1, pad=1,
                   groups=1, flags=0) -> int:

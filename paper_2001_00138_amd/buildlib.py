@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libpatdnn.so")
 PROBES_LIB = os.path.join(HERE, "libpatdnn_probes.so")     # bench-side measurement probes
-SOURCES = ["patdnn_api.hip", "kernel_fkw.hip", "kernel_dw.hip", "kernel_compare.hip", "kernel_tiled.hip", "selftest.hip", "encoder.cpp"]
+SOURCES = ["patdnn_api.hip", "kernel_fkw.hip", "kernel_dw.hip", "kernel_compare.hip", "kernel_tiled.hip", "selftest.hip", "encoder.cpp", "projection.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -36,6 +36,14 @@ patdnn_status_t hip_fail(hipError_t e, const char* what)
     return PATDNN_EHIP;
 }
 
+}  // namespace
+
+namespace patdnn {
+void set_last_error(const std::string& msg) { g_err = msg; }     // for the other translation units
+}
+
+namespace {
+
 struct TiledOnDevice {
     Tiled host;
     DevTiled dev;

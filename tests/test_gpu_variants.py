@@ -110,3 +110,28 @@ def test_pattern_sets_of_other_sizes(torch, oracle, kpat):
         _say(f"    {kpat} patterns cfg={cfg}: rel_err={err:.2e}")
         assert err <= TOL
     L.close()
+
+
+def test_layer_pruned_by_the_projection_operators(torch, oracle):
+    """Magnitude-driven structure instead of random masks: patterns mined from the weights,
+    every kernel projected onto its best pattern, the weakest kernels removed (section 4.1,
+    4.2) - encoded and run, against the oracle on the oracle's own projection of the tensor."""
+    from oracle import projection as proj
+    rng = np.random.default_rng(4242)
+    c_out, c_in = 48, 40
+    w = (rng.standard_normal((c_out, c_in, 3, 3)) * rng.gamma(2.0, 0.1, (c_out, c_in, 1, 1))).astype(np.float32)
+    lib = B.patdnn_mine_patterns(w, 8)
+    ids, z = B.patdnn_project_patterns(w, lib)
+    mask = B.patdnn_project_connectivity(z, wl.round_half_even(c_out * c_in / 3.6))
+    lib_o = proj.mine_pattern_set(w, 8)
+    ids_o, z_o = proj.project_patterns(w, lib_o)
+    mask_o = proj.project_connectivity(z_o, wl.round_half_even(c_out * c_in / 3.6))
+    bias = rng.standard_normal(c_out).astype(np.float32)
+    x = rng.standard_normal((2, c_in, 20, 23)).astype(np.float32)
+    ref = oracle.conv2d(w, ids_o, mask_o, lib_o, x, bias, relu=True)
+    L = B.Layer(w, ids, mask, lib)               # weights outside the patterns are ignored by encode
+    got = L.conv2d(torch.from_numpy(x).cuda(), torch.from_numpy(bias).cuda(), relu=True).cpu().numpy()
+    err = float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
+    _say(f"    projected layer: rel_err={err:.2e}; filter lengths {L.stats()['min_filter_length']}..{L.stats()['max_filter_length']}")
+    assert err <= TOL
+    L.close()
