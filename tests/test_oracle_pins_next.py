@@ -195,3 +195,40 @@ def test_csr_walk_equals_the_definition(stride, pad):
     want = ref.conv2d(w, ids, km, lib, x, b, stride=stride, pad=pad, relu=True)
     got = ocsr.csr_conv2d(*ocsr.build_csr(w, ids, km, lib), x, b, stride=stride, pad=pad, relu=True)
     assert np.abs(got - want).max() <= 1e-12 * max(1.0, float(np.abs(want).max()))
+
+
+# ---------------------------------------------------------------------------- fp16 storage
+def test_binary16_rounding_hand_values_and_library():
+    """The storage rounding the fp16 oracle relies on, against values fixed by the format
+    (10 fraction bits: spacing 2 above 2048, ties to even; largest finite 65504; smallest
+    subnormal 2^-24) and against torch's conversion."""
+    import torch
+    from oracle import fp16
+    cases = [(2049.0, 2048.0), (2051.0, 2052.0), (2050.0, 2050.0), (1.0 + 2.0 ** -11, 1.0),
+             (1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -9), (65504.0, 65504.0), (65519.9, 65504.0), (65520.0, np.inf),
+             (2.0 ** -24, 2.0 ** -24), (2.0 ** -25, 0.0), (1.5 * 2.0 ** -24, 2.0 ** -23), (-0.1, -0.0999755859375)]
+    for x, want in cases:
+        got = float(fp16.to_f16(np.float64(x)))
+        assert got == want, (x, got, want)
+    rng = np.random.default_rng(16)
+    x = (rng.standard_normal(20000) * 10.0 ** rng.integers(-6, 5, 20000)).astype(np.float32)
+    np.testing.assert_array_equal(fp16.to_f16(x).view(np.uint16),
+                                  torch.from_numpy(x).half().numpy().view(np.uint16))
+
+
+def test_fp16_conv_is_the_definition_on_stored_values():
+    """Independent route: torch conv2d in float64 on the binary16-rounded tensors (torch's
+    own rounding), rounded once at the end."""
+    import torch
+    from oracle import fp16
+    rng = np.random.default_rng(17)
+    w, ids, km, lib = _layer(rng, 6, 5, 0.6)
+    x = rng.standard_normal((2, 5, 9, 8)).astype(np.float32)
+    b = rng.standard_normal(6).astype(np.float32)
+    got16, exact = fp16.conv2d_f16(w, ids, km, lib, x, b, relu=True)
+    wm = ref.masked_weights(torch.from_numpy(w).half().float().numpy(), ids, km, lib)
+    y = torch.relu(torch.nn.functional.conv2d(torch.from_numpy(x).half().double(), torch.from_numpy(wm).double(),
+                                              torch.from_numpy(b).double(), padding=1))
+    assert float((torch.from_numpy(exact) - y).abs().max()) <= 1e-12 * float(y.abs().max())
+    # rounding once at the end: within half a binary16 spacing of the exact value
+    assert np.all(np.abs(got16.astype(np.float64) - exact) <= 2.0 ** -11 * np.maximum(np.abs(exact), 2.0 ** -14))
