@@ -307,6 +307,26 @@ def main() -> int:
                               "sum_ms_median": round(tot_ms, 4),
                               "nz_gflops": round(sum(ly["nz"] for ly in st) / (tot_ms * 1e-3) / 1e9, 1),
                               "alg_gbps": round(sum(ly["bytes"] for ly in st) / (tot_ms * 1e-3) / 1e9, 1)}
+                if cfg_no == 4 and batch > 1:
+                    # the same layers on half-precision storage (section 6.1): half the bytes
+                    rows16 = []
+                    for ly in st:
+                        x16, o16 = ly["x"].half(), ly["out"].half()
+                        fn = lambda ly=ly, x16=x16, o16=o16: ly["L"].conv2d_f16(x16, ly["bias"], o16, relu=True)
+                        fn()
+                        ms = sorted(timed_ms(fn, 20))
+                        med = ms[len(ms) // 2]
+                        by16 = ly["bytes"] / 2
+                        rows16.append({"layer": ly["spec"].name, "ms_median": round(med, 4), "ms_min": round(ms[0], 4),
+                                       "alg_gbps": round(by16 / (med * 1e-3) / 1e9, 1),
+                                       "frac_hbm_peak": round(by16 / (med * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)})
+                        del x16, o16
+                    tot16 = sum(r["ms_median"] for r in rows16)
+                    other[key + "_f16_storage"] = {
+                        "workload": other[key]["workload"] + ", binary16 weights / input / output, fp32 arithmetic",
+                        "batch": batch, "layers": rows16, "sum_ms_median": round(tot16, 4),
+                        "alg_gbps": round(sum(ly["bytes"] for ly in st) / 2 / (tot16 * 1e-3) / 1e9, 1),
+                        "speedup_over_fp32_storage": round(tot_ms / tot16, 2)}
                 for ly in st:
                     ly["L"].close()
                 del st

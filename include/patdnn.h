@@ -122,6 +122,19 @@ patdnn_status_t patdnn_conv2d(patdnn_handle_t h, const float* input, int32_t n, 
                               int32_t fuse_relu, void* stream);
 
 /*
+ * The layer on half-precision storage, as the paper's GPU runs keep weights and intermediate
+ * results (section 6.1): `input` and `output` are DEVICE tensors of IEEE binary16 values
+ * (same shapes and layout as patdnn_conv2d, 2 bytes per element), the weights are the
+ * handle's fp32 weights rounded to binary16 (nearest, ties to even; done once by
+ * patdnn_encode), the bias stays fp32, every product and sum is fp32, and the result is
+ * rounded to binary16 once when it is stored.  Depthwise layers run the depthwise kernel
+ * (bound by HBM bandwidth: half the bytes, about half the time); all other layers run the
+ * filter-major FKW kernel - the tiled kernels are fp32 only.  Otherwise as patdnn_conv2d.
+ */
+patdnn_status_t patdnn_conv2d_f16(patdnn_handle_t h, const void* input, int32_t n, int32_t h_in, int32_t w_in,
+                                  const float* bias, void* output, int32_t fuse_relu, void* stream);
+
+/*
  * The layer followed by ReLU and 2x2 max pooling with stride 2 (an odd last row / column
  * is dropped), fused: the CONV stages of the networks the paper runs end in a pooling
  * layer (section 2.1, section 6.2) and only the pooled tensor is written.

@@ -23,7 +23,7 @@ PATDNN_VARIANT_FKW = 0
 
 EXPORTS = [
     "patdnn_mine_patterns", "patdnn_project_patterns", "patdnn_project_connectivity",
-    "patdnn_encode", "patdnn_conv2d", "patdnn_conv2d_pool", "patdnn_output_shape", "patdnn_decode",
+    "patdnn_encode", "patdnn_conv2d", "patdnn_conv2d_f16", "patdnn_conv2d_pool", "patdnn_output_shape", "patdnn_decode",
     "patdnn_stack_create", "patdnn_stack_output_shape", "patdnn_stack_run", "patdnn_stack_run_static", "patdnn_stack_destroy",
     "patdnn_export_fkw", "patdnn_export_csr", "patdnn_layout_stats", "patdnn_num_variants", "patdnn_variant_name",
     "patdnn_set_config", "patdnn_get_config", "patdnn_tune", "patdnn_tiled_info",
@@ -94,6 +94,7 @@ def lib() -> ctypes.CDLL:
         L.patdnn_mine_patterns.argtypes = [vp, i32, i32, i32, vp, ctypes.POINTER(i32)]
         L.patdnn_project_patterns.argtypes = [vp, i32, i32, vp, i32, vp, vp]
         L.patdnn_project_connectivity.argtypes = [vp, i32, i32, ctypes.c_int64, vp]
+        L.patdnn_conv2d_f16.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp]
         L.patdnn_conv2d_pool.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
         L.patdnn_stack_create.argtypes = [ctypes.POINTER(StackLayer), i32, i32, i32, i32, ctypes.POINTER(vp)]
         L.patdnn_stack_output_shape.argtypes = [vp, ctypes.POINTER(i32 * 4)]
@@ -235,6 +236,24 @@ def patdnn_conv2d(handle: int, x, bias=None, out=None, *, fuse_relu=False, strea
         raise ValueError("bias must be float32 [c_out]")
     _check(lib().patdnn_conv2d(handle, _devptr(x), n, h_in, w_in, _devptr(bias), _devptr(out),
                                int(bool(fuse_relu)), _stream_ptr(stream)))
+    return out
+
+
+def patdnn_conv2d_f16(handle: int, x, bias=None, out=None, *, fuse_relu=False, stream=None):
+    """x, out: float16 device tensors (half-precision storage); bias float32."""
+    import torch
+    if x.dtype != torch.float16 or x.dim() != 4:
+        raise ValueError("input must be a 4-d float16 tensor")
+    n, _, h_in, w_in = x.shape
+    shape = patdnn_output_shape(handle, n, h_in, w_in)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float16, device=x.device)
+    elif tuple(out.shape) != shape or out.dtype != torch.float16:
+        raise ValueError(f"output must be float16 {shape}")
+    if bias is not None and (bias.dtype != torch.float32 or bias.numel() != shape[1]):
+        raise ValueError("bias must be float32 [c_out]")
+    _check(lib().patdnn_conv2d_f16(handle, _devptr(x), n, h_in, w_in, _devptr(bias), _devptr(out),
+                                   int(bool(fuse_relu)), _stream_ptr(stream)))
     return out
 
 
@@ -412,6 +431,9 @@ class Layer:
 
     def conv2d(self, x, bias=None, out=None, *, relu=False, stream=None):
         return patdnn_conv2d(self.handle, x, bias, out, fuse_relu=relu, stream=stream)
+
+    def conv2d_f16(self, x, bias=None, out=None, *, relu=False, stream=None):
+        return patdnn_conv2d_f16(self.handle, x, bias, out, fuse_relu=relu, stream=stream)
 
     def conv2d_pool(self, x, bias=None, out=None, *, stream=None):
         return patdnn_conv2d_pool(self.handle, x, bias, out, stream=stream)

@@ -12,25 +12,58 @@
 // them by pattern, so the lanes of a wavefront share one pattern and skip the same rows
 // and taps together (the `if`s on the pattern mask below are then uniform branches).
 // Bias and ReLU are fused; the result goes to the original channel `reorder[f]`.
+// The same kernel runs on fp32 tensors and on half-precision storage (binary16 weights, input
+// and output, fp32 arithmetic in between - the paper's GPU runs keep weights and intermediate
+// results in 16 bits, section 6.1): there the bytes, and with them the time, halve.
+#include <hip/hip_fp16.h>
+
 #include "kernels.hpp"
 
 namespace patdnn {
 
+template <class T>
 struct DwArgs {
     const int32_t* reorder;      // [c] stored filter -> channel
     const int32_t* dw_mask;      // [c] pattern mask of the stored filter's kernel (0: removed)
-    const float* dw_weight;      // [c][4] its weights, ascending position
-    const float* in;
+    const T* dw_weight;          // [c][4] its weights, ascending position
+    const T* in;
     const float* bias;
-    float* out;
+    T* out;
     int32_t c, h, w, ho, wo, wq, pad, relu;
     long long total;             // n * c * ho * wq lanes
 };
 
-// S: stride.  VEC: rows start 16-byte aligned (w % 4 == 0, aligned base) -> vector loads.
-// VST: output rows 16-byte aligned (wo % 4 == 0, aligned base) -> one vector store.
-template <int S, bool VEC, bool VST>
-__global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs a)
+// element access: one value, or four consecutive ones with one 16-byte (fp32) / 8-byte
+// (binary16) access at an address aligned to that size
+__device__ __forceinline__ float ld1(const float* p) { return *p; }
+__device__ __forceinline__ float ld1(const __half* p) { return __half2float(*p); }
+__device__ __forceinline__ void ld4(const float* p, float& a, float& b, float& c, float& d)
+{
+    const float4 m = *reinterpret_cast<const float4*>(p);
+    a = m.x; b = m.y; c = m.z; d = m.w;
+}
+__device__ __forceinline__ void ld4(const __half* p, float& a, float& b, float& c, float& d)
+{
+    const uint2 m = *reinterpret_cast<const uint2*>(p);
+    const __half2 lo = *reinterpret_cast<const __half2*>(&m.x), hi = *reinterpret_cast<const __half2*>(&m.y);
+    a = __low2float(lo); b = __high2float(lo); c = __low2float(hi); d = __high2float(hi);
+}
+__device__ __forceinline__ void st1(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st1(__half* p, float v) { *p = __float2half_rn(v); }
+__device__ __forceinline__ void st4(float* p, const float (&v)[4]) { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
+__device__ __forceinline__ void st4(__half* p, const float (&v)[4])
+{
+    const __half2 lo = __floats2half2_rn(v[0], v[1]), hi = __floats2half2_rn(v[2], v[3]);
+    uint2 m;
+    m.x = *reinterpret_cast<const unsigned*>(&lo);
+    m.y = *reinterpret_cast<const unsigned*>(&hi);
+    *reinterpret_cast<uint2*>(p) = m;
+}
+
+// S: stride.  VEC: rows start aligned to four elements (w % 4 == 0, aligned base) -> vector loads.
+// VST: output rows aligned to four elements (wo % 4 == 0, aligned base) -> one vector store.
+template <int S, bool VEC, bool VST, class T>
+__global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs<T> a)
 {
     constexpr int NC = 3 * S + 3;                  // input columns under four outputs: 6 or 9
     const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
@@ -43,8 +76,9 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs a)
     const long long n = r / a.c;
     const int co = a.reorder[f];
     const unsigned mask = (unsigned)a.dw_mask[f];
-    const float4 wv = reinterpret_cast<const float4*>(a.dw_weight)[f];
-    const float* plane = a.in + ((size_t)n * a.c + co) * ((size_t)a.h * a.w);
+    float4 wv;
+    ld4(a.dw_weight + (size_t)f * 4, wv.x, wv.y, wv.z, wv.w);
+    const T* plane = a.in + ((size_t)n * a.c + co) * ((size_t)a.h * a.w);
     const int ox0 = xq * 4;
     const int ix0 = ox0 * S - a.pad;               // input column under (output ox0, tap 0)
 
@@ -55,29 +89,29 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs a)
         if (rowbits == 0) continue;
         const int iy = oy * S + dy - a.pad;
         if (iy < 0 || iy >= a.h) continue;         // zero padding: the row contributes nothing
-        const float* row = plane + (size_t)iy * a.w;
+        const T* row = plane + (size_t)iy * a.w;
         float v[NC];
         if constexpr (VEC) {
             // pad is 0 or 1: columns ix0 + pad .. are 16-byte aligned
             if (a.pad == 1) {
-                v[0] = ((rowbits & 1u) && ix0 >= 0) ? row[ix0] : 0.0f;
+                v[0] = ((rowbits & 1u) && ix0 >= 0) ? ld1(row + ix0) : 0.0f;
 #pragma unroll
                 for (int q = 0; q < (NC - 1) / 4; ++q) {
                     const int ix = ix0 + 1 + 4 * q;
                     float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (ix < a.w) m = *reinterpret_cast<const float4*>(row + ix);
+                    if (ix < a.w) ld4(row + ix, m.x, m.y, m.z, m.w);
                     v[1 + 4 * q] = m.x; v[2 + 4 * q] = m.y; v[3 + 4 * q] = m.z; v[4 + 4 * q] = m.w;
                 }
                 if constexpr (S == 1) {
                     const int ix = ix0 + 5;
-                    v[5] = ((rowbits & 4u) && ix < a.w) ? row[ix] : 0.0f;
+                    v[5] = ((rowbits & 4u) && ix < a.w) ? ld1(row + ix) : 0.0f;
                 }
             } else {
 #pragma unroll
                 for (int q = 0; q < (NC + 3) / 4; ++q) {
                     const int ix = ix0 + 4 * q;
                     float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (ix < a.w) m = *reinterpret_cast<const float4*>(row + ix);
+                    if (ix < a.w) ld4(row + ix, m.x, m.y, m.z, m.w);
                     if (4 * q + 0 < NC) v[4 * q + 0] = m.x;
                     if (4 * q + 1 < NC) v[4 * q + 1] = m.y;
                     if (4 * q + 2 < NC) v[4 * q + 2] = m.z;
@@ -88,7 +122,7 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs a)
 #pragma unroll
             for (int j = 0; j < NC; ++j) {
                 const int ix = ix0 + j;
-                v[j] = (ix >= 0 && ix < a.w) ? row[ix] : 0.0f;
+                v[j] = (ix >= 0 && ix < a.w) ? ld1(row + ix) : 0.0f;
             }
         }
 #pragma unroll
@@ -107,33 +141,35 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs a)
         acc[i] += b;
         if (a.relu) acc[i] = fmaxf(acc[i], 0.0f);
     }
-    float* dst = a.out + (((size_t)n * a.c + co) * a.ho + oy) * (size_t)a.wo + ox0;
+    T* dst = a.out + (((size_t)n * a.c + co) * a.ho + oy) * (size_t)a.wo + ox0;
     if constexpr (VST) {
-        *reinterpret_cast<float4*>(dst) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        st4(dst, acc);
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if (ox0 + i < a.wo) dst[i] = acc[i];
+            if (ox0 + i < a.wo) st1(dst + i, acc[i]);
     }
 }
 
-hipError_t launch_dw(const DevFkw& f, const ConvShape& s, const float* in, const float* bias,
-                     float* out, hipStream_t stream)
+template <class T>
+static hipError_t launch_dw_t(const DevFkw& f, const T* weights, const ConvShape& s, const T* in, const float* bias,
+                              T* out, hipStream_t stream)
 {
-    DwArgs a{};
-    a.reorder = f.reorder; a.dw_mask = f.dw_mask; a.dw_weight = f.dw_weight;
+    DwArgs<T> a{};
+    a.reorder = f.reorder; a.dw_mask = f.dw_mask; a.dw_weight = weights;
     a.in = in; a.bias = bias; a.out = out;
     a.c = s.c_out; a.h = s.h; a.w = s.w; a.ho = s.ho; a.wo = s.wo;
     a.wq = (s.wo + 3) / 4; a.pad = s.pad; a.relu = s.relu;
     a.total = (long long)s.n * s.c_out * s.ho * a.wq;
     const long long blocks = (a.total + 255) / 256;
     if (blocks > 0x7FFFFFFFll) return hipErrorInvalidValue;
-    // vector loads need every row to start 16-byte aligned and to be read in whole vectors:
-    // the columns a lane reads beyond its last tap stay inside the row when w % 4 == 0
-    const bool vec = s.w % 4 == 0 && (reinterpret_cast<uintptr_t>(in) & 15u) == 0;
-    const bool vst = s.wo % 4 == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0;
+    // vector loads need every row to start aligned to four elements and to be read in whole
+    // vectors: the columns a lane reads beyond its last tap stay inside the row when w % 4 == 0
+    constexpr uintptr_t kAlign = 4 * sizeof(T) - 1;
+    const bool vec = s.w % 4 == 0 && (reinterpret_cast<uintptr_t>(in) & kAlign) == 0;
+    const bool vst = s.wo % 4 == 0 && (reinterpret_cast<uintptr_t>(out) & kAlign) == 0;
     const dim3 grid((unsigned)blocks), block(256);
-#define PATDNN_DW_LAUNCH(S, V, T) hipLaunchKernelGGL((dw_conv_kernel<S, V, T>), grid, block, 0, stream, a)
+#define PATDNN_DW_LAUNCH(S, V, W) hipLaunchKernelGGL((dw_conv_kernel<S, V, W, T>), grid, block, 0, stream, a)
     if (s.stride == 1) {
         if (vec && vst) PATDNN_DW_LAUNCH(1, true, true);
         else if (vec) PATDNN_DW_LAUNCH(1, true, false);
@@ -147,6 +183,19 @@ hipError_t launch_dw(const DevFkw& f, const ConvShape& s, const float* in, const
     }
 #undef PATDNN_DW_LAUNCH
     return hipGetLastError();
+}
+
+hipError_t launch_dw(const DevFkw& f, const ConvShape& s, const float* in, const float* bias,
+                     float* out, hipStream_t stream)
+{
+    return launch_dw_t<float>(f, f.dw_weight, s, in, bias, out, stream);
+}
+
+hipError_t launch_dw_f16(const DevFkw& f, const ConvShape& s, const void* in, const float* bias,
+                         void* out, hipStream_t stream)
+{
+    return launch_dw_t<__half>(f, static_cast<const __half*>(f.dw_weight_f16), s, static_cast<const __half*>(in), bias,
+                               static_cast<__half*>(out), stream);
 }
 
 }  // namespace patdnn

@@ -36,6 +36,10 @@ struct DevFkw {
     // kernel was removed) and its four weights
     const int32_t* dw_mask = nullptr;
     const float* dw_weight = nullptr;
+    // the weights once more as IEEE binary16 (round to nearest even), for the
+    // half-precision-storage entry point: `weight` and `dw_weight` element for element
+    const void* weight_f16 = nullptr;
+    const void* dw_weight_f16 = nullptr;
 };
 
 // Filter-group layout on the device: record streams (sparse) or 9-tap weights (dense).
@@ -68,6 +72,11 @@ hipError_t launch_compare(bool csr, const DevCompare& d, const ConvShape& s, con
 // Depthwise layers: one pass over input and output, 16-byte accesses, four outputs per lane.
 hipError_t launch_dw(const DevFkw& f, const ConvShape& s, const float* in, const float* bias,
                      float* out, hipStream_t stream);
+// The same two kernels on binary16 tensors and weights (fp32 arithmetic, fp32 bias).
+hipError_t launch_dw_f16(const DevFkw& f, const ConvShape& s, const void* in, const float* bias,
+                         void* out, hipStream_t stream);
+hipError_t launch_fkw_f16(const DevFkw& f, const ConvShape& s, const void* in, const float* bias,
+                          void* out, hipStream_t stream);
 
 // ---------------------------------------------------------------------------
 // Tiled kernels: compile-time geometry per variant, run-time launch parameters.

@@ -372,6 +372,17 @@ patdnn_status_t patdnn_encode(const patdnn_layer_desc_t* desc, const float* dens
             return hip_fail(e, "uploading the FKW arrays");
         h->dfkw.num_patterns = f.num_patterns;
         h->dfkw.taps = f.taps;
+        {
+            // the weights once more in binary16 (round to nearest even) for patdnn_conv2d_f16
+            std::vector<uint16_t> w16(f.weight.size());
+            for (size_t i = 0; i < w16.size(); ++i) {
+                const _Float16 hv = static_cast<_Float16>(f.weight[i]);
+                std::memcpy(&w16[i], &hv, 2);
+            }
+            const uint16_t* dev16 = nullptr;
+            if ((e = upload(h->allocations, w16, &dev16)) != hipSuccess) return hip_fail(e, "uploading the binary16 weights");
+            h->dfkw.weight_f16 = dev16;
+        }
         if (h->L.depthwise) {
             // per stored filter: the mask of its kernel's pattern and its four weights
             const int c = desc->c_out, P = f.num_patterns;
@@ -384,9 +395,17 @@ patdnn_status_t patdnn_encode(const patdnn_layer_desc_t* desc, const float* dens
                     if (st[p + 1] > st[p]) dmask[s] = f.masks[p];
                 for (int t = 0; t < 4; ++t) dweight[(size_t)s * 4 + t] = f.weight[(size_t)f.offset[s] * 4 + t];
             }
+            std::vector<uint16_t> dweight16(dweight.size());
+            for (size_t i = 0; i < dweight16.size(); ++i) {
+                const _Float16 hv = static_cast<_Float16>(dweight[i]);
+                std::memcpy(&dweight16[i], &hv, 2);
+            }
+            const uint16_t* dev16 = nullptr;
             if ((e = upload(h->allocations, dmask, &h->dfkw.dw_mask)) != hipSuccess ||
-                (e = upload(h->allocations, dweight, &h->dfkw.dw_weight)) != hipSuccess)
+                (e = upload(h->allocations, dweight, &h->dfkw.dw_weight)) != hipSuccess ||
+                (e = upload(h->allocations, dweight16, &dev16)) != hipSuccess)
                 return hip_fail(e, "uploading the depthwise arrays");
+            h->dfkw.dw_weight_f16 = dev16;
         }
         h->on_device = true;
     }
@@ -471,6 +490,31 @@ patdnn_status_t patdnn_conv2d(patdnn_handle_t h, const float* input, int32_t n, 
                               void* stream)
 {
     return conv2d_impl(h, input, n, h_in, w_in, bias, output, fuse_relu, 0, static_cast<hipStream_t>(stream));
+}
+
+patdnn_status_t patdnn_conv2d_f16(patdnn_handle_t h, const void* input, int32_t n, int32_t h_in, int32_t w_in,
+                                  const float* bias, void* output, int32_t fuse_relu, void* stream)
+{
+    ConvShape s{};
+    patdnn_status_t st = shape_of(h, n, h_in, w_in, s);
+    if (st != PATDNN_OK) return st;
+    if (!h->on_device) return fail(PATDNN_EHIP, "handle was encoded with PATDNN_HOST_ONLY");
+    if (n == 0) return PATDNN_OK;
+    if (!input || !output) return fail(PATDNN_EINVAL, "input / output is NULL");
+    if ((reinterpret_cast<uintptr_t>(input) | reinterpret_cast<uintptr_t>(output)) & 1u)
+        return fail(PATDNN_EINVAL, "binary16 tensors must be 2-byte aligned");
+    {
+        const char* in_lo = static_cast<const char*>(input);
+        const char* in_hi = in_lo + 2ull * (size_t)n * s.c_in * s.h * s.w;
+        const char* out_lo = static_cast<const char*>(output);
+        const char* out_hi = out_lo + 2ull * (size_t)n * s.c_out * s.ho * s.wo;
+        if (in_lo < out_hi && out_lo < in_hi) return fail(PATDNN_EINVAL, "output overlaps input");
+    }
+    s.relu = fuse_relu ? 1 : 0;
+    hipError_t e = h->L.depthwise
+                       ? launch_dw_f16(h->dfkw, s, input, bias, output, static_cast<hipStream_t>(stream))
+                       : launch_fkw_f16(h->dfkw, s, input, bias, output, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching a binary16 kernel");
 }
 
 patdnn_status_t patdnn_conv2d_pool(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
