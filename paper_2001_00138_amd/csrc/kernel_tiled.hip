@@ -312,7 +312,55 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     }
 
     // ---- epilogue: bias, ReLU, scatter to the original output channel
-    if (group_ok && band_ok) {
+    if constexpr (SPLITK && PC == 2 && 64 % (TGX * PC) == 0) {
+        // Partial sums go out as atomic adds, which run at full rate only on whole runs of
+        // consecutive floats: 16 lanes on 16 neighbouring outputs cost next to nothing, the
+        // same values written lane by lane (a lane's two outputs of a row are neighbours, so
+        // one instruction touches every second float of its lines) cost 0.15 ms per 25 MB.
+        // The lanes therefore trade values first: instruction h = 0, 1 of a row covers the
+        // rows of half the wavefront's bands, TGX*PC consecutive lanes per band row, each lane
+        // taking its column from the lane that accumulated it.  The exchange runs with every
+        // lane of the wavefront (outside the per-lane conditions); only the atomics are
+        // predicated.
+        if (group_ok) {
+            constexpr int BW = TGX * PC;                 // columns of a band row
+            constexpr int BPI = 64 / BW;                 // band rows per instruction
+            const size_t oplane = (size_t)a.ho * a.wo;
+            int src[2], rows_left[2];
+            bool odd[2], ok[2];
+            size_t off[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int tb = h * BPI + lane / BW;      // band of the wavefront this lane writes
+                const int col = lane - (lane / BW) * BW;
+                const int owner = (tb * TGX) << 2;       // its first lane: ox0 there is the band's first column
+                const int t_img = __builtin_amdgcn_ds_bpermute(owner, img);
+                const int t_oy0 = __builtin_amdgcn_ds_bpermute(owner, oy0);
+                const int t_x0 = __builtin_amdgcn_ds_bpermute(owner, ox0);
+                const int t_ok = __builtin_amdgcn_ds_bpermute(owner, band_ok ? 1 : 0);
+                src[h] = owner + ((col >> 1) << 2);
+                odd[h] = (col & 1) != 0;
+                ok[h] = t_ok != 0 && t_x0 + col < a.wo;
+                rows_left[h] = a.ho - t_oy0;
+                off[h] = ((size_t)t_img * a.c_out * a.ho + t_oy0) * (size_t)a.wo + t_x0 + col;
+            }
+#pragma unroll
+            for (int s = 0; s < G; ++s) {
+                const int co = load_uniform(a.slot_channel, group * G + s);
+                if (co < 0) continue;
+                float* dst = a.out + (size_t)co * oplane;
+#pragma unroll
+                for (int r = 0; r < PR; ++r) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const float even = __int_as_float(__builtin_amdgcn_ds_bpermute(src[h], __float_as_int(acc[s][r * PC])));
+                        const float oddv = __int_as_float(__builtin_amdgcn_ds_bpermute(src[h], __float_as_int(acc[s][r * PC + 1])));
+                        if (ok[h] && r < rows_left[h]) unsafeAtomicAdd(&dst[off[h] + (size_t)r * a.wo], odd[h] ? oddv : even);
+                    }
+                }
+            }
+        }
+    } else if (group_ok && band_ok) {
         const size_t oplane = (size_t)a.ho * a.wo;
         if (!SPLITK && a.pool) {
             // ReLU + 2x2 max pooling: fold every value into its pooled cell (zero beforehand)

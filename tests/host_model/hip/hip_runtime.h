@@ -54,6 +54,8 @@ struct State {
     long errors = 0;
     std::string first_error;
     pthread_barrier_t barrier;
+    pthread_barrier_t wave_barrier[16];   // one per wavefront of the workgroup (lane exchanges)
+    int exchange[16][64];
     pthread_mutex_t lock = PTHREAD_MUTEX_INITIALIZER;
 };
 State& state();
@@ -106,6 +108,34 @@ inline unsigned __float_as_uint(float f)
     unsigned u;
     __builtin_memcpy(&u, &f, 4);
     return u;
+}
+
+inline int __float_as_int(float f)
+{
+    int i;
+    __builtin_memcpy(&i, &f, 4);
+    return i;
+}
+inline float __int_as_float(int i)
+{
+    float f;
+    __builtin_memcpy(&f, &i, 4);
+    return f;
+}
+
+// ds_bpermute_b32: every lane of the wavefront takes `value` of lane (addr / 4) % 64.  All 64
+// lanes (OS threads) of the wavefront must call it together, as on the hardware with a full
+// EXEC mask; a lane that stayed away would leave the others at the barrier, so a kernel
+// that calls it under a per-lane condition hangs here instead of passing by luck.
+inline int __builtin_amdgcn_ds_bpermute(int addr, int value)
+{
+    hostmodel::State& st = hostmodel::state();
+    const unsigned wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    st.exchange[wave][lane] = value;
+    pthread_barrier_wait(&st.wave_barrier[wave]);
+    const int got = st.exchange[wave][((unsigned)addr >> 2) & 63];
+    pthread_barrier_wait(&st.wave_barrier[wave]);
+    return got;
 }
 
 #define __builtin_amdgcn_readfirstlane(x) (x)
@@ -163,6 +193,7 @@ void hostmodel_launch(void (*kernel)(Args...), dim3 grid, dim3 block, size_t lds
         const uint32_t poison = 0x7FC0DEADu;                 // NaN: reading unstaged LDS shows in the output
         for (size_t i = 0; i < kLdsFloats; ++i) std::memcpy(&patdnn::lds[i], &poison, 4);
         pthread_barrier_init(&st.barrier, nullptr, block.x);
+        for (unsigned w = 0; w < block.x / 64; ++w) pthread_barrier_init(&st.wave_barrier[w], nullptr, 64);
         std::vector<std::thread> threads;
         for (unsigned t = 0; t < block.x; ++t)
             threads.emplace_back([=]() {
@@ -171,6 +202,7 @@ void hostmodel_launch(void (*kernel)(Args...), dim3 grid, dim3 block, size_t lds
             });
         for (auto& th : threads) th.join();
         pthread_barrier_destroy(&st.barrier);
+        for (unsigned w = 0; w < block.x / 64; ++w) pthread_barrier_destroy(&st.wave_barrier[w]);
     }
 }
 #define hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, ...) \
