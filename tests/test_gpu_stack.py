@@ -66,7 +66,12 @@ def test_fused_pool_on_every_variant(torch, oracle, case):
         numel = int(np.prod(ref.shape))
         buf = torch.full((numel + 2 * guard,), 777.0, dtype=torch.float32, device="cuda")
         out = buf[guard:guard + numel].view(ref.shape)
-        L.conv2d_pool(xt, bt, out)
+        try:
+            L.conv2d_pool(xt, bt, out)
+        except B.PatdnnError as e:
+            # the comparison kernels (no-opt, CSR) have no pooled epilogue and say so
+            assert e.status == B.PATDNN_EUNSUPPORTED and B.patdnn_variant_name(v) in ("noopt", "csr")
+            continue
         full = L.conv2d(xt, bt, relu=True)
         torch.cuda.synchronize()
         assert bool((buf[:guard] == 777.0).all()) and bool((buf[guard + numel:] == 777.0).all())
