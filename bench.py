@@ -225,6 +225,10 @@ def main() -> int:
         name = variant_name(ly["cfg"])
         if ly["spec"].dense or ly["spec"].depthwise:
             continue
+        if ly["cfg"].get("ksplit", 1) > 1:
+            # a channel-split layer is three launches (zero fill, the split instantiation of the
+            # kernel, bias + ReLU): another kernel symbol, kept apart from the unsplit launches
+            name += "+split"
         agg = by_kernel.setdefault(name, dict(ms=0.0, flops=0, bytes=0, launches=0))
         agg["ms"] += per_layer_ms[k]
         agg["flops"] += ly["nz"]
@@ -249,10 +253,10 @@ def main() -> int:
         }
         # HBM bytes per launch from hardware counters, if a counter run of this command was summarised
         try:
-            ly0 = next(ly for ly in layers if variant_name(ly["cfg"]) == kname)
+            ly0 = next(ly for ly in layers if variant_name(ly["cfg"]) == kname.replace("+split", ""))
             info = B.patdnn_tiled_info(ly0["L"].handle, ly0["cfg"]["variant"], ly0["cfg"]["ck"])
             sig = re.compile(rf"Geo<{info['G']}, {info['patch_rows']}, {info['patch_cols']}, {info['conv_stride']}, "
-                             rf"{info['lanes_x']}, false, \d+, {info['mode']}>, false>")
+                             rf"{info['lanes_x']}, false, \d+, {info['mode']}>, {'true' if kname.endswith('+split') else 'false'}>")
             with open(args.traffic_json) as f:
                 table = json.load(f)
             hit = [v for k, v in table.items() if sig.search(k) and "fetch_bytes" in v and "write_bytes" in v]

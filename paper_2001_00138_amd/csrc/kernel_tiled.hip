@@ -28,7 +28,10 @@
 //     9-tap loop and no stream.
 #include <algorithm>
 #include <atomic>
+#include <cstdlib>
+#include <mutex>
 #include <type_traits>
+#include <vector>
 
 #include "kernels.hpp"
 #include "layout.hpp"
@@ -45,6 +48,11 @@ struct TiledArgs {
     const float* w9;
     int32_t n, c_in, c_out, h, w, ho, wo, pad, relu, pool;
     int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets;
+    // issue priority (see the kernel): workgroups with a linear index >= late_from are in the
+    // last round of the launch and run one level higher per late_span workgroups; late_span 0
+    // with late_from 0 = the launch is a single round, priority follows the remaining work;
+    // late_from INT32_MAX = every wavefront stays at the default priority
+    int32_t late_from, late_span;
 #ifdef PATDNN_TIMELINE
     unsigned long long* tl;      // [blocks][8 waves][8 phases] cycle totals (debug builds only)
 #endif
@@ -250,12 +258,37 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     // workgroups per CU); the chunk is loaded after everyone has left the previous one and
     // the other workgroups of the CU cover the wait.  Otherwise two alternating buffers.
     constexpr bool ONE_BUFFER = (GEO::MODE & 16) != 0;
+    // ---- issue priority.  A SIMD serves its oldest wavefront first, so the wavefronts that
+    // start last (the last round of workgroups, dispatched as the earlier ones retire) crawl
+    // behind their older neighbours and then finish alone, at a third of the SIMD's rate: the
+    // launch ends one lonely wavefront life after the machine has run out of work.  The
+    // workgroups of the last round therefore issue at raised priority, the later dispatched
+    // the higher (levels 1..3 over the round), and the launch ends close to the time its
+    // last-dispatched workgroup needs on its own.  A launch of a single round has no late
+    // workgroups; there the priority follows the remaining work (set per chunk below), so that
+    // the wavefronts sharing a SIMD finish together instead of one after the other.
+    const int late = (int)(blockIdx.y * gridDim.x + blockIdx.x) - a.late_from;
+    if (late >= 0 && a.late_span > 0) {
+        const int level = late / a.late_span;
+        if (level == 0) __builtin_amdgcn_s_setprio(1);
+        else if (level == 1) __builtin_amdgcn_s_setprio(2);
+        else __builtin_amdgcn_s_setprio(3);
+    }
     TL_MARK(0);                                   // prologue
     if constexpr (!ONE_BUFFER) stage(c_first, lds3);
     TL_MARK(2);
     for (int c0 = c_first, chunk = SPLITK ? chunk_first : 0; c0 < c_end; c0 += a.ck, ++chunk) {
         const int cn = min(a.ck, a.c_in - c0);
         const int cur = ONE_BUFFER ? 0 : ((SPLITK ? chunk - chunk_first : chunk) & 1) * buf_floats;
+        if (a.late_span == 0 && a.late_from == 0) {
+            // single round: the wavefronts that are behind issue first
+            const int total = (c_end - c_first + a.ck - 1) / a.ck;
+            const int q = (4 * ((c0 - c_first) / a.ck)) / total;
+            if (q == 0) __builtin_amdgcn_s_setprio(3);
+            else if (q == 1) __builtin_amdgcn_s_setprio(2);
+            else if (q == 2) __builtin_amdgcn_s_setprio(1);
+            else __builtin_amdgcn_s_setprio(0);
+        }
         if constexpr (ONE_BUFFER) {
             __syncthreads();                      // everyone has finished reading the buffer
             stage(c0, lds3);
@@ -467,6 +500,38 @@ __global__ __launch_bounds__(256) void bias_relu_pool_kernel(const float* sum, c
     }
 }
 
+// Workgroups of `fn` that the current device holds at once with this block size and dynamic
+// LDS (0 if the runtime cannot say).  Asked once per (device, kernel, block size, LDS size).
+static long long resident_workgroups(const void* fn, int threads, size_t lds_bytes)
+{
+    struct Entry { int dev; const void* fn; int threads; size_t lds; long long slots; };
+    static std::mutex lock;
+    static std::vector<Entry> known;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    std::lock_guard<std::mutex> guard(lock);
+    for (const Entry& e : known)
+        if (e.dev == dev && e.fn == fn && e.threads == threads && e.lds == lds_bytes) return e.slots;
+    int per_cu = 0, cus = 0;
+    long long slots = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, threads, lds_bytes) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+        slots = (long long)per_cu * cus;
+    known.push_back(Entry{dev, fn, threads, lds_bytes, slots});
+    return slots;
+}
+
+// PATDNN_WAVE_PRIORITY=0 in the environment leaves every wavefront at the default priority
+// (for measuring what the priorities buy); read once.
+static bool wave_priority_enabled()
+{
+    static const bool on = [] {
+        const char* e = std::getenv("PATDNN_WAVE_PRIORITY");
+        return !(e && e[0] == '0' && e[1] == 0);
+    }();
+    return on;
+}
+
 template <class GEO>
 static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const float* in,
                                const float* bias, float* out, int32_t waves, int32_t ksplit,
@@ -498,6 +563,23 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
         static std::atomic<uint64_t> allowed{0};
         hipError_t e = allow_big_lds(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, false>), allowed);
         if (e != hipSuccess) return e;
+    }
+    {
+        // workgroups of this launch that are resident at once, for the issue priorities
+        const long long all = blocks * (ksplit > 1 ? ksplit : 1);
+        const void* fn = ksplit > 1 ? reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, true>)
+                                    : reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, false>);
+        const long long slots = wave_priority_enabled() ? resident_workgroups(fn, 64 * waves, lds_bytes) : 0;
+        a.late_from = INT32_MAX;
+        a.late_span = 0;
+        if (slots > 0) {
+            if (all <= slots) {
+                a.late_from = 0;                                   // a single round: by remaining work
+            } else {
+                a.late_from = (int32_t)(all - slots);
+                a.late_span = (int32_t)((slots + 2) / 3);
+            }
+        }
     }
     if (s.pool && ksplit > 1 && !scratch) return hipErrorInvalidValue;   // the slices need somewhere to add up
     if (ksplit <= 1) {

@@ -40,6 +40,10 @@ constexpr int hipFuncAttributeMaxDynamicSharedMemorySize = 8;
 inline hipError_t hipGetLastError() { return hipSuccess; }
 inline hipError_t hipFuncSetAttribute(const void*, int, int) { return hipSuccess; }
 inline hipError_t hipGetDevice(int* d) { *d = 0; return hipSuccess; }
+// a small machine, so that the launches of the tests span several rounds of workgroups
+enum hipDeviceAttribute_t { hipDeviceAttributeMultiprocessorCount = 0 };
+inline hipError_t hipDeviceGetAttribute(int* v, hipDeviceAttribute_t, int) { *v = 2; return hipSuccess; }
+inline hipError_t hipOccupancyMaxActiveBlocksPerMultiprocessor(int* n, const void*, int, size_t) { *n = 3; return hipSuccess; }
 
 namespace hostmodel {
 
@@ -140,6 +144,7 @@ inline int __builtin_amdgcn_ds_bpermute(int addr, int value)
 
 #define __builtin_amdgcn_readfirstlane(x) (x)
 #define __builtin_amdgcn_s_waitcnt(x) ((void)0)
+#define __builtin_amdgcn_s_setprio(x) ((void)0)     // issue arbitration only: no effect on results
 
 // ---- raw buffer descriptor and the LDS-direct load
 struct __amdgpu_buffer_rsrc_t {
