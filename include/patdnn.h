@@ -226,6 +226,9 @@ patdnn_status_t patdnn_layout_stats(patdnn_handle_t h, patdnn_stats_t* out);
  * slices handled by different workgroups, whose partial sums are added into the output
  * with atomic adds between a zero-fill and a bias + ReLU kernel (three launches; the
  * summation order then varies from run to run within fp32 rounding); 0 or 1 = off.
+ * The environment variable PATDNN_WAVE_PRIORITY=0 (read once per process) switches off
+ * the issue priorities that the tiled kernels give the workgroups of their last round; it
+ * changes timing only, never results.
  */
 typedef struct {
     int32_t variant;
