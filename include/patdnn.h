@@ -248,9 +248,10 @@ patdnn_status_t patdnn_get_config(patdnn_handle_t h, patdnn_config_t* cfg);
 /*
  * Parameter auto-tuning (section 5.5), reduced to an exhaustive timed search over
  * the variants and launch parameters that can run this layer at this input size.
- * Runs every candidate on the caller's buffers (a few runs each, the fastest four again
- * with more runs; output ends up holding a valid result of the winner), synchronises the
- * stream, keeps the fastest in the handle and reports it.  `best_us` may be NULL.
+ * Runs every candidate on the caller's buffers (a few runs each; the fastest four again in
+ * alternating turns, judged by the median of their turns; output ends up holding a valid
+ * result of the winner), synchronises the stream, keeps the fastest in the handle and
+ * reports its time.  `best_us` may be NULL.
  */
 patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
                             int32_t w_in, const float* bias, float* output, void* stream,

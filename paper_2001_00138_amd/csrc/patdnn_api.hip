@@ -785,7 +785,9 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
         ms /= (float)reps;
         return PATDNN_OK;
     };
-    // first pass over every candidate, then the four fastest again with more runs: the
+    // first pass over every candidate, then the four fastest again, in turns (clocks and cache
+    // contents drift while a process tunes: a candidate timed later is not timed under the
+    // same conditions as one timed earlier), each judged by the median of its turns: the
     // winner of a noisy first pass should not stay by luck
     std::vector<std::pair<float, size_t>> timed;
     for (size_t i = 0; i < cands.size(); ++i) {
@@ -796,10 +798,19 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
     }
     if (result == PATDNN_OK) {
         std::sort(timed.begin(), timed.end());
-        for (size_t k = 0; k < timed.size() && k < 4; ++k) {
-            float ms = 0.0f;
-            st = time_config(cands[timed[k].second], 8, ms);
-            if (st != PATDNN_OK) { result = st; break; }
+        const size_t finalists = std::min<size_t>(timed.size(), 4);
+        constexpr int kTurns = 5;
+        std::vector<std::vector<float>> turns(finalists);
+        for (int t = 0; t < kTurns && result == PATDNN_OK; ++t)
+            for (size_t k = 0; k < finalists; ++k) {
+                float ms = 0.0f;
+                st = time_config(cands[timed[k].second], 3, ms);
+                if (st != PATDNN_OK) { result = st; break; }
+                turns[k].push_back(ms);
+            }
+        for (size_t k = 0; k < finalists && result == PATDNN_OK; ++k) {
+            std::sort(turns[k].begin(), turns[k].end());
+            const float ms = turns[k][turns[k].size() / 2];
             if (best < 0.0f || ms < best) { best = ms; best_cfg = cands[timed[k].second]; }
         }
     }
