@@ -325,11 +325,28 @@ patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const Conv
     return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching a tiled kernel");
 }
 
+// Tiled variants in the order in which an untuned layer tries them: first the variant that the
+// tuner prefers on most measured layers (threaded dispatch, 7x2 patch, one staging buffer; it
+// needs the scalar relative moves that the self-test checks on the device), then the order
+// of variants.def, whose first line (call dispatch) has no such requirement.
+std::vector<int> default_variant_order(const patdnn_layer* h)
+{
+    std::vector<int> order;
+    for (int vi = 0; vi < num_tiled_variants(); ++vi)
+        if (std::string(tiled_variant(vi).name) == "t_g8_p7x2_s1_x8_thw1b") {
+            std::string why;
+            if (!h->on_device || movrel_selftest(why)) order.push_back(vi);
+        }
+    for (int vi = 0; vi < num_tiled_variants(); ++vi)
+        if (order.empty() || vi != order[0]) order.push_back(vi);
+    return order;
+}
+
 // The configuration used when the caller has not chosen or tuned one.
 patdnn_config_t default_config(patdnn_layer* h, const ConvShape& s)
 {
     if (h->L.depthwise) return patdnn_config_t{variant_of_extra(kExtraDepthwise), 0, 0, 1};
-    for (int vi = 0; vi < num_tiled_variants(); ++vi) {
+    for (int vi : default_variant_order(h)) {
         const TiledVariant& v = tiled_variant(vi);
         if (!variant_selectable(h, v)) continue;
         int32_t ck = 0, waves = 0;
@@ -412,7 +429,7 @@ patdnn_status_t patdnn_encode(const patdnn_layer_desc_t* desc, const float* dens
     // build (and upload) the group layout of the default variant; the layouts of the other
     // variants are built when patdnn_set_config or patdnn_tune asks for them
     try {
-        for (int vi = 0; vi < num_tiled_variants(); ++vi)
+        for (int vi : default_variant_order(h.get()))
             if (variant_selectable(h.get(), tiled_variant(vi))) {
                 st = ensure_tiled(h.get(), vi, default_ck(tiled_variant(vi), desc->c_in), nullptr);
                 if (st != PATDNN_OK) return st;
