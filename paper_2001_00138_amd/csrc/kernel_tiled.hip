@@ -574,7 +574,8 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
         a.late_span = 0;
         if (slots > 0) {
             if (all <= slots) {
-                a.late_from = 0;                                   // a single round: by remaining work
+                // a single round: by remaining work - where wavefronts share SIMDs at all
+                if (2 * all > slots) a.late_from = 0;
             } else {
                 a.late_from = (int32_t)(all - slots);
                 a.late_span = (int32_t)((slots + 2) / 3);
