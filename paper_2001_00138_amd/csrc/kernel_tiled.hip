@@ -564,26 +564,24 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
         hipError_t e = allow_big_lds(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, false>), allowed);
         if (e != hipSuccess) return e;
     }
-    {
-        // workgroups of this launch that are resident at once, for the issue priorities
-        const long long all = blocks * (ksplit > 1 ? ksplit : 1);
-        const void* fn = ksplit > 1 ? reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, true>)
-                                    : reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, false>);
+    // issue priorities from the workgroups of this launch that are resident at once (asked
+    // after the kernel has been allowed its dynamic LDS: the answer depends on it)
+    auto set_priorities = [&](const void* fn, long long all) {
         const long long slots = wave_priority_enabled() ? resident_workgroups(fn, 64 * waves, lds_bytes) : 0;
         a.late_from = INT32_MAX;
         a.late_span = 0;
-        if (slots > 0) {
-            if (all <= slots) {
-                // a single round: by remaining work - where wavefronts share SIMDs at all
-                if (2 * all > slots) a.late_from = 0;
-            } else {
-                a.late_from = (int32_t)(all - slots);
-                a.late_span = (int32_t)((slots + 2) / 3);
-            }
+        if (slots <= 0) return;
+        if (all <= slots) {
+            // a single round: by remaining work - where wavefronts share SIMDs at all
+            if (2 * all > slots) a.late_from = 0;
+        } else {
+            a.late_from = (int32_t)(all - slots);
+            a.late_span = (int32_t)((slots + 2) / 3);
         }
-    }
+    };
     if (s.pool && ksplit > 1 && !scratch) return hipErrorInvalidValue;   // the slices need somewhere to add up
     if (ksplit <= 1) {
+        set_priorities(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, false>), blocks);
         hipLaunchKernelGGL((tiled_conv_kernel<GEO, false>), dim3((unsigned)blocks), dim3(64 * waves), lds_bytes,
                            stream, a);
         return hipGetLastError();
@@ -598,6 +596,7 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
             hipError_t e = allow_big_lds(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, true>), allowed_k);
             if (e != hipSuccess) return e;
         }
+        set_priorities(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, true>), blocks * ksplit);
         const size_t plane = (size_t)s.ho * s.wo, total = (size_t)s.n * s.c_out * plane;
         const unsigned fill_blocks = (unsigned)std::min<size_t>((total + 255) / 256, 256 * 32);
         float* sums = s.pool ? scratch : out;
