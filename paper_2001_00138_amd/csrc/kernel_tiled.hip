@@ -414,6 +414,24 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                             atomicMax(&dst[(size_t)(oy >> 1) * pwo + (ox >> 1)], __float_as_uint(v));
                     }
             }
+        } else if (!SPLITK && PC == 2 && (a.wo & 1) == 0 && (reinterpret_cast<uintptr_t>(a.out) & 7) == 0) {
+            // a lane's two outputs of a row are neighbours at an even column: with an even row
+            // length (and an 8-byte aligned tensor) they go out as one 8-byte store
+            struct alignas(8) Pair { float x, y; };
+#pragma unroll
+            for (int s = 0; s < G; ++s) {
+                const int co = load_uniform(a.slot_channel, group * G + s);
+                if (co < 0) continue;
+                const float b = a.bias ? load_uniform(a.bias, co) : 0.0f;
+                float* dst = a.out + ((size_t)img * a.c_out + co) * oplane;
+#pragma unroll
+                for (int r = 0; r < PR; ++r) {
+                    const int oy = oy0 + r;
+                    Pair v{acc[s][r * PC] + b, acc[s][r * PC + 1] + b};
+                    if (a.relu) { v.x = fmaxf(v.x, 0.0f); v.y = fmaxf(v.y, 0.0f); }
+                    if (oy < a.ho && ox0 < a.wo) *reinterpret_cast<Pair*>(&dst[(size_t)oy * a.wo + ox0]) = v;
+                }
+            }
         } else {
 #pragma unroll
             for (int s = 0; s < G; ++s) {

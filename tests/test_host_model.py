@@ -106,6 +106,7 @@ CASES = [
     dict(c_out=16, c_in=6, n=1, h=30, w=37, keep=0.6, ck=4, waves=3, pad=0),
     dict(c_out=20, c_in=12, n=2, h=15, w=18, keep=0.35, ck=5, waves=2, pad=1, stride=2),
     dict(c_out=9, c_in=6, n=1, h=20, w=9, keep=0.5, ck=2, waves=4, pad=0, stride=2),
+    dict(c_out=24, c_in=10, n=2, h=12, w=22, keep=0.4, ck=4, waves=4, pad=1),     # even rows: paired stores
 ]
 
 
