@@ -746,11 +746,12 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
     hipStream_t stream = static_cast<hipStream_t>(stream_);
 
     std::vector<patdnn_config_t> cands;
-    // The grid: chunk sizes 8 and 16 (smaller ones lose to their barrier count, larger ones to
-    // LDS occupancy on every layer measured), 4 or 8 wavefronts per workgroup (fewer only when
+    // The grid: chunk sizes 8, 10 and 16 (smaller ones lose to their barrier count, larger ones
+    // to LDS occupancy on every layer measured; 10 is the most that leaves the single-buffer 7x2
+    // variant three workgroups per CU), 4 or 8 wavefronts per workgroup (fewer only when
     // the layer has fewer filter groups), and input-channel slices only for launches that
     // cannot fill the chip's wavefront slots three times over.
-    const int ck_opts[] = {8, 16};
+    const int ck_opts[] = {8, 10, 16};
     const int wave_opts[] = {1, 2, 4, 8};
     const long long kWaveSlots = 256 * 4 * 3;
     for (int vi = 0; vi < num_tiled_variants(); ++vi) {
