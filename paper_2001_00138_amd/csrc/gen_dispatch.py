@@ -314,15 +314,19 @@ def _program_threaded(G, PR, PC, S, TGX, MODE, g):
             if action:
                 asm(f"v_add_u32 %[addr], s{cur + T_WOFF}, %[lane]")
                 _window_reads(asm, g, (action - 1) if DW else 0)
-                if not DW:
-                    asm("s_waitcnt lgkmcnt(0)")
-            if not DW:
-                fetch(nxt)
-            # first record of the step; M0 = register index (from SET_A) of the second
+            # first record of the step; M0 = register index (from SET_A) of the second; the jump
+            # target.  With one window set this scalar work runs while the window reads are in
+            # flight (the FMAs that read the weight registers were all issued before).
             asm(f"s_mov_b64 s[{W}:{W + 1}], s[{cur}:{cur + 1}]")
             asm(f"s_mov_b64 s[{W + 2}:{W + 3}], s[{cur + 2}:{cur + 3}]")
             asm(f"s_mov_b32 m0, {cur - SET_A + T_REC_DWORDS}")
-            jump(f"s{cur + 4}")
+            asm(f"s_add_u32 s{TGT}, s{BASE}, s{cur + 4}")
+            asm(f"s_addc_u32 s{TGT + 1}, s{BASE + 1}, 0")
+            if not DW:
+                if action:
+                    asm("s_waitcnt lgkmcnt(0)")
+                fetch(nxt)
+            asm(f"s_setpc_b64 s[{TGT}:{TGT + 1}]")
             asm.end_block(ctrl_log2)
     asm.begin_block(ctrl_log2)               # end of the chunk's stream
     asm("s_waitcnt lgkmcnt(0)")              # the step fetched ahead
