@@ -147,7 +147,7 @@ def test_connectivity_projection_is_the_nearest_feasible_tensor():
 
 def test_joint_projection_reaches_the_papers_rates():
     """Pattern projection keeps 4 of 9 weights and connectivity projection 1/3.6 of the
-    kernels: (9/4)*3.6 = 8.1, the paper's "around 8x" for an all-3x3 network (section 4.3)."""
+    kernels: (9/4)*3.6 = 8.1, the roughly eightfold figure the paper gives for an all-3x3 network (section 4.3)."""
     rng = np.random.default_rng(21)
     w = rng.standard_normal((12, 15, 3, 3)).astype(np.float32)
     lib = proj.mine_pattern_set(w, 8)
