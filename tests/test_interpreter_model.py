@@ -195,7 +195,7 @@ def test_model_runs_long_streams(oracle):
     d = wl.gen_layer(3, 4, with_input=False)           # 128 -> 128
     x = wl.gen_input(d["spec"], 3, 4, 1)[:, :, :7, :14]
     seen = _check(oracle, d, x, 8, only={
-        "t_g16_p7x1_s1_x16", "t_g12_p7x1_s1_x16_th", "t_g8_p7x2_s1_x8_thw", "t_g16_p7x1_s1_x7_th",
+        "t_g16_p7x1_s1_x16", "t_g12_p7x1_s1_x16_th", "t_g8_p7x2_s1_x8_thw1b", "t_g16_p7x1_s1_x7_th",
         "t_g16_p7x1_s1_x16_thwb"})
     assert len(seen) == 5
 
@@ -213,7 +213,7 @@ def test_model_runs_every_block_of_the_table(oracle):
          "bias": rng.standard_normal(c_out).astype(np.float32)}
     x = rng.standard_normal((1, c_in, 7, 9)).astype(np.float32)
     seen = _check(oracle, d, x, 14, only={
-        "t_g16_p7x1_s1_x16", "t_g16_p7x1_s1_x16_thwb", "t_g8_p7x2_s1_x8_thw", "t_g12_p7x1_s1_x16_th"})
+        "t_g16_p7x1_s1_x16", "t_g16_p7x1_s1_x16_thwb", "t_g8_p7x2_s1_x8_thw1b", "t_g12_p7x1_s1_x16_th"})
     assert len(seen) == 4
 
 
