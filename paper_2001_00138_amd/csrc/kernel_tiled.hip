@@ -58,6 +58,11 @@ struct TiledArgs {
 #endif
 };
 
+// Phase timeline for performance work: a build with -DPATDNN_TIMELINE makes every wavefront add
+// up the cycles it spends in each phase (prologue, waiting for staged data, issuing staging
+// loads, the chunk's kernels, epilogue, barriers) and write the totals to the buffer given to
+// patdnn_debug_timeline(); the figures in the design notes come from it.  The product build
+// does not define the macro and compiles none of it.
 #ifdef PATDNN_TIMELINE
 #define TL_DECL unsigned long long tl_t = __builtin_readcyclecounter(), tl_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}
 #define TL_MARK(k) do { const unsigned long long now = __builtin_readcyclecounter(); tl_acc[k] += now - tl_t; tl_t = now; } while (0)
