@@ -84,6 +84,59 @@ def test_every_variant_and_ksplit_matches_the_oracle(torch, oracle, case):
     assert seen > 0
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_random_shapes_and_configurations(torch, oracle, seed):
+    """Seeded random layers (channels that are no multiple of anything, tiny and ragged images,
+    stride 1 and 2, pad 0 and 1, with and without bias and ReLU, sparse to fully connected) in the
+    automatic configuration and in a random explicit configuration of every variant that accepts
+    the layer: chunk sizes, workgroup sizes and channel slices off the tuner's grid included."""
+    lib = wl.pattern_library(wl.PATTERN_SEED)
+    runs = 0
+    for case in range(8):
+        rng = np.random.default_rng(1000 * seed + case)
+        c_in = int(rng.choice([3, 5, 8, 16, 24, 33, 64, 96]))
+        c_out = int(rng.choice([4, 8, 13, 16, 24, 40, 64, 72, 128]))
+        h, w, n = int(rng.integers(5, 40)), int(rng.integers(5, 40)), int(rng.integers(1, 7))
+        stride, pad, relu = int(rng.choice([1, 1, 1, 2])), int(rng.choice([0, 1, 1])), bool(rng.integers(0, 2))
+        keep = float(rng.choice([0.1, 0.3, 0.6, 1.0]))
+        ids = rng.integers(0, 8, (c_out, c_in), dtype=np.uint8)
+        mask = (rng.random((c_out, c_in)) < keep).astype(np.uint8)
+        wt = rng.standard_normal((c_out, c_in, 3, 3)).astype(np.float32)
+        bias = rng.standard_normal(c_out).astype(np.float32) if rng.integers(0, 2) else None
+        x = rng.standard_normal((n, c_in, h, w)).astype(np.float32)
+        ref = oracle.conv2d(wt, ids, mask, lib, x, bias, stride=stride, pad=pad, relu=relu, skip_removed=True)
+        scale = max(float(np.abs(ref).max()), 1e-30)
+        L = B.Layer(wt, ids, mask, lib, stride=stride, pad=pad)
+        xt = torch.from_numpy(x).cuda()
+        bt = None if bias is None else torch.from_numpy(bias).cuda()
+        shape = L.output_shape(n, h, w)
+        numel, guard = int(np.prod(shape)), 2048
+        cfgs = [(-1, 0, 0, 1)]
+        for v in range(1, B.patdnn_num_variants()):
+            cfgs.append((v, int(rng.choice([0, 2, 4, 8, 10, 16])), int(rng.choice([0, 3, 4, 8])),
+                         int(rng.choice([1, 1, 2, 3, 5]))))
+        try:
+            for cfg in cfgs:
+                try:
+                    L.set_config(*cfg)
+                except B.PatdnnError as e:
+                    assert e.status in (B.PATDNN_EUNSUPPORTED, B.PATDNN_EINVAL)
+                    continue
+                _say(f"  seed {seed} case {case}: {c_in}->{c_out} @{h}x{w} n={n} s{stride} p{pad} relu={relu} "
+                     f"keep={keep} bias={bias is not None} cfg={cfg}")
+                buf = torch.full((numel + 2 * guard,), 4242.0, dtype=torch.float32, device="cuda")
+                out = buf[guard:guard + numel].view(shape)
+                L.conv2d(xt, bt, out, relu=relu)
+                torch.cuda.synchronize()
+                assert bool((buf[:guard] == 4242.0).all()) and bool((buf[guard + numel:] == 4242.0).all())
+                err = float(np.abs(out.cpu().numpy().astype(np.float64) - ref).max() / scale)
+                assert err <= TOL, (seed, case, cfg, err)
+                runs += 1
+        finally:
+            L.close()
+    assert runs >= 16
+
+
 @pytest.mark.parametrize("kpat", [6, 12, 56])
 def test_pattern_sets_of_other_sizes(torch, oracle, kpat):
     """Libraries of 6, 12 and all 56 patterns (the paper's study of the pattern count,
