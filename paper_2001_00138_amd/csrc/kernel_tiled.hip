@@ -38,6 +38,26 @@
 
 namespace patdnn {
 
+// Division of a value below 2^31 by a launch-time constant d >= 1 without the divider loop:
+// with l = ceil(log2 d) and m = ceil(2^(31+l) / d) (which fits 32 bits), floor(n / d) =
+// (n * m) >> (31 + l) exactly for every n < 2^31 (the error term n * (m*d - 2^(31+l)) /
+// (d * 2^(31+l)) stays below 2^-l <= 1/d).  The kernel's index arithmetic divides band numbers
+// by the bands per image row and column seven times per thread before it can start.
+struct FastDiv {
+    uint32_t m, shift;
+};
+inline FastDiv make_fast_div(uint32_t d)
+{
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    const uint64_t p = 1ull << (31 + l);
+    return FastDiv{(uint32_t)((p + d - 1) / d), 31 + l};
+}
+__host__ __device__ __forceinline__ uint32_t fast_div(uint32_t n, FastDiv f)
+{
+    return (uint32_t)(((uint64_t)n * f.m) >> f.shift);
+}
+
 struct TiledArgs {
     const float* in;
     const float* bias;
@@ -48,6 +68,7 @@ struct TiledArgs {
     const float* w9;
     int32_t n, c_in, c_out, h, w, ho, wo, pad, relu, pool;
     int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets;
+    FastDiv div_bx, div_by;      // for divisions by bx and by
     // issue priority (see the kernel): workgroups with a linear index >= late_from are in the
     // last round of the launch and run one level higher per late_span workgroups; late_span 0
     // with late_from 0 = the launch is a single round, priority follows the remaining work;
@@ -178,8 +199,8 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
         if (q < WR) {
             const int band = band0 + b;
             if (band < a.num_bands) {
-                const int bxi = band % a.bx, t = band / a.bx;
-                const int byi = t % a.by, img = t / a.by;
+                const int t = (int)fast_div((uint32_t)band, a.div_bx), bxi = band - t * a.bx;
+                const int img = (int)fast_div((uint32_t)t, a.div_by), byi = t - img * a.by;
                 const int iy = byi * PR * S - a.pad + q;
                 const int ix = bxi * TGX * PC * S - a.pad + x;
                 if (iy >= 0 && iy < a.h && ix >= 0 && ix < a.w)
@@ -236,9 +257,9 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     const bool band_ok = lane_ok && my_band < a.num_bands;
     int img = 0, oy0 = 0, ox0 = 0;
     if (band_ok) {
-        const int bxi = my_band % a.bx, t = my_band / a.bx;
-        const int byi = t % a.by;
-        img = t / a.by;
+        const int t = (int)fast_div((uint32_t)my_band, a.div_bx), bxi = my_band - t * a.bx;
+        img = (int)fast_div((uint32_t)t, a.div_by);
+        const int byi = t - img * a.by;
         oy0 = byi * PR;
         ox0 = (bxi * TGX + gx) * PC;
     }
@@ -569,6 +590,8 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
     a.num_groups = t.num_groups;
     a.bx = (s.wo + GEO::TGX * GEO::PC - 1) / (GEO::TGX * GEO::PC);
     a.by = (s.ho + GEO::PR - 1) / GEO::PR;
+    a.div_bx = make_fast_div((uint32_t)a.bx);
+    a.div_by = make_fast_div((uint32_t)a.by);
     const long long bands = (long long)s.n * a.bx * a.by;
     const long long tiles = (bands + GEO::NB - 1) / GEO::NB;
     a.num_bands = (int32_t)bands;

@@ -147,6 +147,9 @@ long hostmodel_run(int variant, int G, int num_groups, int ck, int num_chunks, c
     return st.errors;
 }
 
+// The kernel's division by a launch-time constant, as the launcher sets it up.
+unsigned hostmodel_fast_div(unsigned n, unsigned d) { return patdnn::fast_div(n, patdnn::make_fast_div(d)); }
+
 int hostmodel_variant_lds_floats(int variant) { return patdnn::tiled_variant(variant).lds_floats_per_channel; }
 int hostmodel_variant_max_slots(int variant) { return patdnn::tiled_variant(variant).max_slots; }
 

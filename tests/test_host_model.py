@@ -143,6 +143,26 @@ def test_every_sparse_variant_on_the_host_model(hostmodel, oracle, case):
     assert seen >= 2
 
 
+def test_division_by_launch_constants(hostmodel):
+    """The multiply-and-shift that replaces the kernel's divisions by the bands per row and
+    column: exact for every dividend below 2^31, checked at the edges of each quotient step
+    and on random values, for small, large, power-of-two and odd divisors."""
+    f = hostmodel.hostmodel_fast_div
+    f.restype, f.argtypes = ctypes.c_uint, [ctypes.c_uint, ctypes.c_uint]
+    rng = np.random.default_rng(5)
+    top = 2 ** 31 - 1
+    divisors = [1, 2, 3, 4, 5, 7, 8, 9, 14, 16, 28, 32, 33, 100, 255, 256, 257, 1000, 65535, 65536, 65537,
+                10 ** 6, 2 ** 30 - 1, 2 ** 30, 2 ** 30 + 1, top] + [int(v) for v in rng.integers(1, top, 40)]
+    for d in divisors:
+        ns = {0, 1, d - 1, d, d + 1, top, top - 1, top - d if top > d else 0}
+        for q in [int(v) for v in rng.integers(0, top // d + 1, 30)] + [top // d]:
+            ns.update({q * d - 1, q * d, q * d + d - 1})
+        ns.update(int(v) for v in rng.integers(0, top, 200))
+        for n in ns:
+            if 0 <= n <= top:
+                assert f(n, d) == n // d, (n, d)
+
+
 @pytest.mark.parametrize("plant", ["staging column", "epilogue guard", "lane offset"])
 def test_host_model_catches_planted_mistakes(tmp_path, oracle, plant):
     edits = {
