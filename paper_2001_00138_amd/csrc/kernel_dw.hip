@@ -31,6 +31,7 @@ struct DwArgs {
     T* out;
     int32_t c, h, w, ho, wo, wq, pad, relu;
     long long total;             // n * c * ho * wq lanes
+    FastDiv div_wq, div_ho, div_c;   // for lane numbers below 2^31 (every realistic launch)
 };
 
 // element access: one value, or four consecutive ones with one 16-byte (fp32) / 8-byte
@@ -68,12 +69,29 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs<T> a)
     constexpr int NC = 3 * S + 3;                  // input columns under four outputs: 6 or 9
     const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
     if (t >= a.total) return;
-    const int xq = (int)(t % a.wq);
-    long long r = t / a.wq;
-    const int oy = (int)(r % a.ho);
-    r /= a.ho;
-    const int f = (int)(r % a.c);
-    const long long n = r / a.c;
+    // lane number -> (image n, stored channel f, output row oy, group of four columns xq).  A
+    // thread has a dozen FMAs to do, so three 64-bit divisions would be most of its
+    // instructions and the kernel would be bound by them instead of by HBM: below 2^31 lanes
+    // they are multiplications by launch-time constants.
+    int xq, oy, f;
+    long long n;
+    if (a.total <= 0x7FFFFFFFll) {
+        const uint32_t t32 = (uint32_t)t;
+        const uint32_t r1 = fast_div(t32, a.div_wq);
+        xq = (int)(t32 - r1 * (uint32_t)a.wq);
+        const uint32_t r2 = fast_div(r1, a.div_ho);
+        oy = (int)(r1 - r2 * (uint32_t)a.ho);
+        const uint32_t r3 = fast_div(r2, a.div_c);
+        f = (int)(r2 - r3 * (uint32_t)a.c);
+        n = r3;
+    } else {
+        xq = (int)(t % a.wq);
+        long long r = t / a.wq;
+        oy = (int)(r % a.ho);
+        r /= a.ho;
+        f = (int)(r % a.c);
+        n = r / a.c;
+    }
     const int co = a.reorder[f];
     const unsigned mask = (unsigned)a.dw_mask[f];
     float4 wv;
@@ -161,6 +179,9 @@ static hipError_t launch_dw_t(const DevFkw& f, const T* weights, const ConvShape
     a.c = s.c_out; a.h = s.h; a.w = s.w; a.ho = s.ho; a.wo = s.wo;
     a.wq = (s.wo + 3) / 4; a.pad = s.pad; a.relu = s.relu;
     a.total = (long long)s.n * s.c_out * s.ho * a.wq;
+    a.div_wq = make_fast_div((uint32_t)a.wq);
+    a.div_ho = make_fast_div((uint32_t)a.ho);
+    a.div_c = make_fast_div((uint32_t)a.c);
     const long long blocks = (a.total + 255) / 256;
     if (blocks > 0x7FFFFFFFll) return hipErrorInvalidValue;
     // vector loads need every row to start aligned to four elements and to be read in whole

@@ -38,26 +38,6 @@
 
 namespace patdnn {
 
-// Division of a value below 2^31 by a launch-time constant d >= 1 without the divider loop:
-// with l = ceil(log2 d) and m = ceil(2^(31+l) / d) (which fits 32 bits), floor(n / d) =
-// (n * m) >> (31 + l) exactly for every n < 2^31 (the error term n * (m*d - 2^(31+l)) /
-// (d * 2^(31+l)) stays below 2^-l <= 1/d).  The kernel's index arithmetic divides band numbers
-// by the bands per image row and column seven times per thread before it can start.
-struct FastDiv {
-    uint32_t m, shift;
-};
-inline FastDiv make_fast_div(uint32_t d)
-{
-    uint32_t l = 0;
-    while ((1ull << l) < d) ++l;
-    const uint64_t p = 1ull << (31 + l);
-    return FastDiv{(uint32_t)((p + d - 1) / d), 31 + l};
-}
-__host__ __device__ __forceinline__ uint32_t fast_div(uint32_t n, FastDiv f)
-{
-    return (uint32_t)(((uint64_t)n * f.m) >> f.shift);
-}
-
 struct TiledArgs {
     const float* in;
     const float* bias;
