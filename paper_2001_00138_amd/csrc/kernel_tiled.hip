@@ -479,17 +479,61 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(float* p, size_t n)
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.0f;
 }
 
-// out[n][c][pixel] = act(out + bias[c]) in place, after the split kernels have added up
-__global__ __launch_bounds__(256) void bias_act_kernel(float* out, const float* bias, int c_out, size_t plane,
-                                                       size_t total, int relu)
+// out[n][c][pixel] = act(out + bias[c]) in place, after the split kernels have added up.
+// A unit is VEC floats of one plane (VEC = 4 where planes are whole aligned float4s); which
+// channel a unit belongs to comes from multiplications where the count allows (a 64-bit
+// division per element would cost more than the memory traffic of a small layer).
+struct FinishArgs {
+    size_t plane_units, total_units;
+    FastDiv div_plane, div_c;            // used when total_units < 2^31
+    int c_out, relu;
+};
+
+template <int VEC>
+__global__ __launch_bounds__(256) void bias_act_kernel(float* out, const float* bias, FinishArgs a)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-        float v = out[i];
-        if (bias) v += bias[(i / plane) % (size_t)c_out];
-        if (relu) v = fmaxf(v, 0.0f);
-        out[i] = v;
+    const bool small = a.total_units <= 0x7FFFFFFFull;
+    for (size_t u = (size_t)blockIdx.x * blockDim.x + threadIdx.x; u < a.total_units; u += stride) {
+        float b = 0.0f;
+        if (bias) {
+            size_t c;
+            if (small) {
+                const uint32_t pl = fast_div((uint32_t)u, a.div_plane);
+                c = pl - fast_div(pl, a.div_c) * (uint32_t)a.c_out;
+            } else {
+                c = (u / a.plane_units) % (size_t)a.c_out;
+            }
+            b = bias[c];
+        }
+        if constexpr (VEC == 4) {
+            float4 v = reinterpret_cast<float4*>(out)[u];
+            v.x += b; v.y += b; v.z += b; v.w += b;
+            if (a.relu) { v.x = fmaxf(v.x, 0.0f); v.y = fmaxf(v.y, 0.0f); v.z = fmaxf(v.z, 0.0f); v.w = fmaxf(v.w, 0.0f); }
+            reinterpret_cast<float4*>(out)[u] = v;
+        } else {
+            float v = out[u] + b;
+            if (a.relu) v = fmaxf(v, 0.0f);
+            out[u] = v;
+        }
     }
+}
+
+static void launch_bias_act(float* out, const float* bias, int c_out, size_t plane, size_t total, int relu,
+                            hipStream_t stream)
+{
+    const bool vec = plane % 4 == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
+    FinishArgs a{};
+    a.plane_units = vec ? plane / 4 : plane;
+    a.total_units = vec ? total / 4 : total;
+    a.div_plane = make_fast_div((uint32_t)std::min<size_t>(a.plane_units, 0x7FFFFFFFu));
+    a.div_c = make_fast_div((uint32_t)c_out);
+    a.c_out = c_out;
+    a.relu = relu;
+    const unsigned blocks = (unsigned)std::min<size_t>((a.total_units + 255) / 256, 256 * 32);
+    if (blocks == 0) return;
+    if (vec) hipLaunchKernelGGL(bias_act_kernel<4>, dim3(blocks), dim3(256), 0, stream, out, bias, a);
+    else hipLaunchKernelGGL(bias_act_kernel<1>, dim3(blocks), dim3(256), 0, stream, out, bias, a);
 }
 
 // More than 64 KB of dynamic LDS needs the function attribute, once per device (bit = device
@@ -509,15 +553,29 @@ static hipError_t allow_big_lds(const void* fn, std::atomic<uint64_t>& done)
 // out[n][c][py][px] = max over the 2x2 window of relu(sum[n][c][2py+dy][2px+dx] + bias[c]):
 // finishes a split-channel launch whose partial sums were added up in `sum`
 __global__ __launch_bounds__(256) void bias_relu_pool_kernel(const float* sum, const float* bias, float* out,
-                                                             int c_out, int ho, int wo, int pho, int pwo, size_t total)
+                                                             int c_out, int ho, int wo, int pho, int pwo, size_t total,
+                                                             FastDiv div_pwo, FastDiv div_pho, FastDiv div_c)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const bool small = total <= 0x7FFFFFFFull;      // then the divisions are multiplications
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-        const int px = (int)(i % pwo);
-        size_t r = i / pwo;
-        const int py = (int)(r % pho);
-        r /= pho;                                   // n * c_out + c
-        const float b = bias ? bias[r % (size_t)c_out] : 0.0f;
+        int px, py;
+        size_t r, c;                                // r = n * c_out + c
+        if (small) {
+            const uint32_t r1 = fast_div((uint32_t)i, div_pwo);
+            px = (int)((uint32_t)i - r1 * (uint32_t)pwo);
+            const uint32_t r2 = fast_div(r1, div_pho);
+            py = (int)(r1 - r2 * (uint32_t)pho);
+            r = r2;
+            c = r2 - fast_div(r2, div_c) * (uint32_t)c_out;
+        } else {
+            px = (int)(i % pwo);
+            r = i / pwo;
+            py = (int)(r % pho);
+            r /= pho;
+            c = r % (size_t)c_out;
+        }
+        const float b = bias ? bias[c] : 0.0f;
         const float* src = sum + (r * ho + 2 * py) * (size_t)wo + 2 * px;
         const float m = fmaxf(fmaxf(src[0], src[1]), fmaxf(src[wo], src[wo + 1]));
         out[i] = fmaxf(m + b, 0.0f);
@@ -637,10 +695,11 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
             const unsigned pblocks = (unsigned)std::min<size_t>((ptotal + 255) / 256, 256 * 32);
             // max(relu(x + b)) over a window = relu(max(x) + b): one bias add and one ReLU per cell
             hipLaunchKernelGGL(bias_relu_pool_kernel, dim3(pblocks), dim3(256), 0, stream,
-                               static_cast<const float*>(sums), bias, out, s.c_out, s.ho, s.wo, pho, pwo, ptotal);
+                               static_cast<const float*>(sums), bias, out, s.c_out, s.ho, s.wo, pho, pwo, ptotal,
+                               make_fast_div((uint32_t)std::max(pwo, 1)), make_fast_div((uint32_t)std::max(pho, 1)),
+                               make_fast_div((uint32_t)s.c_out));
         } else {
-            hipLaunchKernelGGL(bias_act_kernel, dim3(fill_blocks), dim3(256), 0, stream, out, bias, s.c_out, plane,
-                               total, s.relu);
+            launch_bias_act(out, bias, s.c_out, plane, total, s.relu, stream);
         }
         return hipGetLastError();
     }

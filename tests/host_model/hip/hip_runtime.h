@@ -37,6 +37,7 @@ typedef int hipError_t;
 typedef void* hipStream_t;
 constexpr hipError_t hipSuccess = 0, hipErrorInvalidValue = 1;
 constexpr int hipFuncAttributeMaxDynamicSharedMemorySize = 8;
+struct alignas(16) float4 { float x, y, z, w; };
 inline hipError_t hipGetLastError() { return hipSuccess; }
 inline hipError_t hipFuncSetAttribute(const void*, int, int) { return hipSuccess; }
 inline hipError_t hipGetDevice(int* d) { *d = 0; return hipSuccess; }
