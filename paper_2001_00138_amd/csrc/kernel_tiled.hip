@@ -48,7 +48,7 @@ struct TiledArgs {
     const float* w9;
     int32_t n, c_in, c_out, h, w, ho, wo, pad, relu, pool;
     int32_t num_groups, bx, by, num_bands, ck, num_chunks, waves, fgsets;
-    FastDiv div_bx, div_by;      // for divisions by bx and by
+    FastDiv div_bx, div_by, div_fgsets, div_bxby;   // for divisions by bx, by, fgsets and bx*by
     // issue priority (see the kernel): workgroups with a linear index >= late_from are in the
     // last round of the launch and run one level higher per late_span workgroups; late_span 0
     // with late_from 0 = the launch is a single round, priority follows the remaining work;
@@ -145,14 +145,14 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     const int nblk = gridDim.x;
     const int per_xcd = nblk >> 3, xcd = blockIdx.x & 7, rank = blockIdx.x >> 3;
     const int bid = rank < per_xcd ? xcd * per_xcd + rank : blockIdx.x;   // tail (< 8 blocks) keeps its id
-    const int tile = bid / a.fgsets;
+    const int tile = (int)fast_div((uint32_t)bid, a.div_fgsets);
     const int fgset = bid - tile * a.fgsets;
     const int group = fgset * a.waves + wave;
     const int band0 = tile * NB;
     const int plane = a.h * a.w;
 
     // image of the tile's first band: staging offsets are relative to it
-    const int img0 = band0 / (a.bx * a.by);
+    const int img0 = (int)fast_div((uint32_t)band0, a.div_bxby);
     const float* in_blk = a.in + (size_t)img0 * a.c_in * plane;
 
     // ---- staging slots of this thread: byte offset (inside the tile's first image
@@ -253,12 +253,14 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
 
     const bool group_ok = group < a.num_groups;
 
-    int chunk_first = 0, c_first = 0, c_end = a.c_in;
+    int chunk_first = 0, c_first = 0, c_end = a.c_in, chunks_here = a.num_chunks;
     if constexpr (SPLITK) {
         const int k = (int)gridDim.y, y = (int)blockIdx.y;
         chunk_first = (int)((long long)a.num_chunks * y / k);
+        const int chunk_last = (int)((long long)a.num_chunks * (y + 1) / k);
+        chunks_here = chunk_last - chunk_first;
         c_first = chunk_first * a.ck;
-        c_end = min(a.c_in, (int)((long long)a.num_chunks * (y + 1) / k) * a.ck);
+        c_end = min(a.c_in, chunk_last * a.ck);
     }
     // MODE bit 4: ONE staging buffer (half the LDS, so twice the channels per chunk or more
     // workgroups per CU); the chunk is loaded after everyone has left the previous one and
@@ -287,12 +289,12 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
         const int cn = min(a.ck, a.c_in - c0);
         const int cur = ONE_BUFFER ? 0 : ((SPLITK ? chunk - chunk_first : chunk) & 1) * buf_floats;
         if (a.late_span == 0 && a.late_from == 0) {
-            // single round: the wavefronts that are behind issue first
-            const int total = (c_end - c_first + a.ck - 1) / a.ck;
-            const int q = (4 * ((c0 - c_first) / a.ck)) / total;
-            if (q == 0) __builtin_amdgcn_s_setprio(3);
-            else if (q == 1) __builtin_amdgcn_s_setprio(2);
-            else if (q == 2) __builtin_amdgcn_s_setprio(1);
+            // single round: the wavefronts that are behind issue first (quarters of the
+            // slice's chunks, by comparison: no division in the loop)
+            const int done4 = 4 * (chunk - (SPLITK ? chunk_first : 0));
+            if (done4 < chunks_here) __builtin_amdgcn_s_setprio(3);
+            else if (done4 < 2 * chunks_here) __builtin_amdgcn_s_setprio(2);
+            else if (done4 < 3 * chunks_here) __builtin_amdgcn_s_setprio(1);
             else __builtin_amdgcn_s_setprio(0);
         }
         if constexpr (ONE_BUFFER) {
@@ -630,11 +632,13 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
     a.by = (s.ho + GEO::PR - 1) / GEO::PR;
     a.div_bx = make_fast_div((uint32_t)a.bx);
     a.div_by = make_fast_div((uint32_t)a.by);
+    a.div_bxby = make_fast_div((uint32_t)a.bx * (uint32_t)a.by);
     const long long bands = (long long)s.n * a.bx * a.by;
     const long long tiles = (bands + GEO::NB - 1) / GEO::NB;
     a.num_bands = (int32_t)bands;
     a.ck = t.ck; a.num_chunks = t.num_chunks; a.waves = waves;
     a.fgsets = (t.num_groups + waves - 1) / waves;
+    a.div_fgsets = make_fast_div((uint32_t)a.fgsets);
 #ifdef PATDNN_TIMELINE
     a.tl = g_timeline;
 #endif
