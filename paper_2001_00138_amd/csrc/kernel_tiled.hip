@@ -486,6 +486,8 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(float* p, size_t n)
 // channel a unit belongs to comes from multiplications where the count allows (a 64-bit
 // division per element would cost more than the memory traffic of a small layer).
 struct FinishArgs {
+    float* zero;                         // also cleared by this launch (the next launch's target), or NULL
+    size_t zero_count;
     size_t plane_units, total_units;
     FastDiv div_plane, div_c;            // used when total_units < 2^31
     int c_out, relu;
@@ -496,6 +498,7 @@ __global__ __launch_bounds__(256) void bias_act_kernel(float* out, const float* 
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     const bool small = a.total_units <= 0x7FFFFFFFull;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < a.zero_count; i += stride) a.zero[i] = 0.0f;
     for (size_t u = (size_t)blockIdx.x * blockDim.x + threadIdx.x; u < a.total_units; u += stride) {
         float b = 0.0f;
         if (bias) {
@@ -522,17 +525,19 @@ __global__ __launch_bounds__(256) void bias_act_kernel(float* out, const float* 
 }
 
 static void launch_bias_act(float* out, const float* bias, int c_out, size_t plane, size_t total, int relu,
-                            hipStream_t stream)
+                            float* zero, size_t zero_count, hipStream_t stream)
 {
     const bool vec = plane % 4 == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
     FinishArgs a{};
+    a.zero = zero;
+    a.zero_count = zero ? zero_count : 0;
     a.plane_units = vec ? plane / 4 : plane;
     a.total_units = vec ? total / 4 : total;
     a.div_plane = make_fast_div((uint32_t)std::min<size_t>(a.plane_units, 0x7FFFFFFFu));
     a.div_c = make_fast_div((uint32_t)c_out);
     a.c_out = c_out;
     a.relu = relu;
-    const unsigned blocks = (unsigned)std::min<size_t>((a.total_units + 255) / 256, 256 * 32);
+    const unsigned blocks = (unsigned)std::min<size_t>((std::max(a.total_units, a.zero_count / 4) + 255) / 256, 256 * 32);
     if (blocks == 0) return;
     if (vec) hipLaunchKernelGGL(bias_act_kernel<4>, dim3(blocks), dim3(256), 0, stream, out, bias, a);
     else hipLaunchKernelGGL(bias_act_kernel<1>, dim3(blocks), dim3(256), 0, stream, out, bias, a);
@@ -556,10 +561,13 @@ static hipError_t allow_big_lds(const void* fn, std::atomic<uint64_t>& done)
 // finishes a split-channel launch whose partial sums were added up in `sum`
 __global__ __launch_bounds__(256) void bias_relu_pool_kernel(const float* sum, const float* bias, float* out,
                                                              int c_out, int ho, int wo, int pho, int pwo, size_t total,
-                                                             FastDiv div_pwo, FastDiv div_pho, FastDiv div_c)
+                                                             FastDiv div_pwo, FastDiv div_pho, FastDiv div_c,
+                                                             float* zero, size_t zero_count)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     const bool small = total <= 0x7FFFFFFFull;      // then the divisions are multiplications
+    // the next launch's target, cleared here to save it a launch (never the sums read below)
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < zero_count; i += stride) zero[i] = 0.0f;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
         int px, py;
         size_t r, c;                                // r = n * c_out + c
@@ -690,20 +698,26 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
         float* sums = s.pool ? scratch : out;
         a.out = sums;
         a.pool = 0;                                  // the slices add plain partial sums
-        hipLaunchKernelGGL(fill_zero_kernel, dim3(fill_blocks), dim3(256), 0, stream, sums, total);
+        if (!(s.pre_zeroed == sums && s.pre_zeroed_count >= total))
+            hipLaunchKernelGGL(fill_zero_kernel, dim3(fill_blocks), dim3(256), 0, stream, sums, total);
+        // the finishing kernel below may clear the next launch's target on the way, unless that
+        // is the very buffer it reads the sums from
+        float* zero_next = (s.zero_next && s.zero_next != sums) ? s.zero_next : nullptr;
+        const size_t zero_next_count = zero_next ? s.zero_next_count : 0;
+        if (zero_next && s.zero_next_done) *s.zero_next_done = true;
         hipLaunchKernelGGL((tiled_conv_kernel<GEO, true>), dim3((unsigned)blocks, (unsigned)ksplit), dim3(64 * waves),
                            lds_bytes, stream, a);
         if (s.pool) {
             const int pho = s.ho / 2, pwo = s.wo / 2;
             const size_t ptotal = (size_t)s.n * s.c_out * pho * pwo;
-            const unsigned pblocks = (unsigned)std::min<size_t>((ptotal + 255) / 256, 256 * 32);
+            const unsigned pblocks = (unsigned)std::min<size_t>((std::max(ptotal, zero_next_count) + 255) / 256, 256 * 32);
             // max(relu(x + b)) over a window = relu(max(x) + b): one bias add and one ReLU per cell
             hipLaunchKernelGGL(bias_relu_pool_kernel, dim3(pblocks), dim3(256), 0, stream,
                                static_cast<const float*>(sums), bias, out, s.c_out, s.ho, s.wo, pho, pwo, ptotal,
                                make_fast_div((uint32_t)std::max(pwo, 1)), make_fast_div((uint32_t)std::max(pho, 1)),
-                               make_fast_div((uint32_t)s.c_out));
+                               make_fast_div((uint32_t)s.c_out), zero_next, zero_next_count);
         } else {
-            launch_bias_act(out, bias, s.c_out, plane, total, s.relu, stream);
+            launch_bias_act(out, bias, s.c_out, plane, total, s.relu, zero_next, zero_next_count, stream);
         }
         return hipGetLastError();
     }

@@ -17,6 +17,20 @@ struct ConvShape {
     // starts: every lane folds its values in with an unsigned integer atomic max on the
     // float bits, which orders non-negative floats like the floats themselves.
     int32_t pool = 0;
+    // Zero-fill hand-off between consecutive launches of a stack (all optional).  The launches
+    // that add into their target with atomics (split, pooled) need it zeroed beforehand, which
+    // costs a kernel launch of its own; a launch that ends with a finishing kernel can clear
+    // the next launch's target in that same kernel instead.
+    //   pre_zeroed / pre_zeroed_count: a region that already holds zeros on entry; a zero fill of
+    //     exactly that region (same start, no more floats) is skipped.
+    //   zero_next / zero_next_count: a region to clear in this launch's finishing kernel, if it
+    //     has one and the region is not one the kernel still reads; *zero_next_done is set when
+    //     it was cleared (left alone otherwise).
+    const float* pre_zeroed = nullptr;
+    size_t pre_zeroed_count = 0;
+    float* zero_next = nullptr;
+    size_t zero_next_count = 0;
+    bool* zero_next_done = nullptr;
 };
 
 // Fills `count` floats with zero (a kernel, so that it can be captured into a HIP graph).
