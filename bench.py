@@ -292,6 +292,42 @@ def main() -> int:
         if roofline is not None:
             roofline["frac_of_measured_fma_loop"] = round(roofline["achieved"] / fma_tflops, 4)
 
+    # ------------------------------------------------------------------ the same step as two half batches
+    # The images of a batch are independent, so a caller may send one half of the batch through
+    # all layers on one stream and the other half on a second one: the launches of one half then
+    # cover the ends of the other half's launches, where the machine runs out of workgroups.
+    # Reported beside the headline, which stays one stream (there a launch's duration is the
+    # kernel's own, which is what the roofline row divides by).
+    halves = None
+    if not args.only_timed and layers[0]["spec"].n >= 2:
+        n_img = layers[0]["spec"].n
+        side = [torch.cuda.Stream(), torch.cuda.Stream()]
+        cut = [0, n_img // 2, n_img]
+
+        def step_halves():
+            fork = torch.cuda.Event()
+            fork.record(stream)
+            for p, st in enumerate(side):
+                st.wait_event(fork)
+                for ly in layers:
+                    ly["L"].conv2d(ly["x"][cut[p]:cut[p + 1]], ly["bias"], ly["out"][cut[p]:cut[p + 1]],
+                                   relu=True, stream=st)
+                join = torch.cuda.Event()
+                join.record(st)
+                stream.wait_event(join)
+
+        for _ in range(min(args.warmup, 3)):
+            step_halves()
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(args.steps):
+            step_halves()
+        torch.cuda.synchronize()
+        ms_h = (time.perf_counter() - c0) * 1e3 / args.steps
+        halves = {"ms_per_step": round(ms_h, 4), "nz_gflops": round(total_nz / (ms_h * 1e-3) / 1e9, 1),
+                  "note": "the batch as two halves on two streams, each half through all layers in order, "
+                          "joined at the end of every step; same kernels and configurations"}
+
     # ------------------------------------------------------------------ the other stacks, per layer
     other = None
     if not args.no_other_stacks and args.config == 5:
@@ -563,6 +599,7 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
         "measured_peaks": peaks,
+        "two_stream_halves": halves,
         "batch1_stack_latency": latency,
         "layers": layer_rows,
         "other_stacks": other,
