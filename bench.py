@@ -100,6 +100,10 @@ def main() -> int:
         # variant -1: the library picks its default configuration at every call
         return B.patdnn_variant_name(cfg["variant"]) if cfg["variant"] >= 0 else "auto"
 
+    # Workspace for the layers whose configuration splits the input channels (one buffer of
+    # partial sums per slice); shared by every launch on `stream`, which run one after the other.
+    ws = torch.empty(64 << 20, dtype=torch.float32, device="cuda")          # 256 MB
+
     saved = wl.load_tuned_configs(args.configs) if not args.tune else {}
     used_configs = dict(saved)
     names = {B.patdnn_variant_name(v): v for v in range(B.patdnn_num_variants())}
@@ -111,7 +115,7 @@ def main() -> int:
         if c is not None and c["variant"] in names:
             L.set_config(names[c["variant"]], c["ck"], c["waves"], c["ksplit"])
         elif not args.no_tune:
-            L.tune(x, bias, out)
+            L.tune(x, bias, out, workspace=ws)
         cfg = L.get_config()
         if cfg["variant"] >= 0:
             used_configs[key] = dict(cfg, variant=B.patdnn_variant_name(cfg["variant"]))
@@ -181,7 +185,7 @@ def main() -> int:
         for k, ly in enumerate(layers):
             if events is not None:
                 events[k][0].record(stream)
-            ly["L"].conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+            ly["L"].conv2d_ws(ly["x"], ly["bias"], ly["out"], workspace=ws, relu=True)
             if events is not None:
                 events[k][1].record(stream)
 
@@ -226,8 +230,9 @@ def main() -> int:
         if ly["spec"].dense or ly["spec"].depthwise:
             continue
         if ly["cfg"].get("ksplit", 1) > 1:
-            # a channel-split layer is three launches (zero fill, the split instantiation of the
-            # kernel, bias + ReLU): another kernel symbol, kept apart from the unsplit launches
+            # a channel-split layer is two launches (the split instantiation of the kernel, whose
+            # slices store to the workspace, then sum + bias + ReLU): another kernel symbol, kept
+            # apart from the unsplit launches
             name += "+split"
         agg = by_kernel.setdefault(name, dict(ms=0.0, flops=0, bytes=0, launches=0))
         agg["ms"] += per_layer_ms[k]
@@ -302,6 +307,7 @@ def main() -> int:
     if not args.only_timed and layers[0]["spec"].n >= 2:
         n_img = layers[0]["spec"].n
         side = [torch.cuda.Stream(), torch.cuda.Stream()]
+        side_ws = [ws[:ws.numel() // 2], ws[ws.numel() // 2:]]       # launches of the two streams overlap
         cut = [0, n_img // 2, n_img]
 
         def step_halves():
@@ -310,8 +316,8 @@ def main() -> int:
             for p, st in enumerate(side):
                 st.wait_event(fork)
                 for ly in layers:
-                    ly["L"].conv2d(ly["x"][cut[p]:cut[p + 1]], ly["bias"], ly["out"][cut[p]:cut[p + 1]],
-                                   relu=True, stream=st)
+                    ly["L"].conv2d_ws(ly["x"][cut[p]:cut[p + 1]], ly["bias"], ly["out"][cut[p]:cut[p + 1]],
+                                      workspace=side_ws[p], relu=True, stream=st)
                 join = torch.cuda.Event()
                 join.record(st)
                 stream.wait_event(join)
@@ -338,7 +344,7 @@ def main() -> int:
                 st = build_stack(cfg_no, batch, per_image_input=False)
                 rows = []
                 for ly in st:
-                    fn = lambda ly=ly: ly["L"].conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+                    fn = lambda ly=ly: ly["L"].conv2d_ws(ly["x"], ly["bias"], ly["out"], workspace=ws, relu=True)
                     fn()
                     rows.append(layer_row(ly, timed_ms(fn, 20)))
                     if cfg_no == 4 and batch > 1:
@@ -355,7 +361,7 @@ def main() -> int:
                         def rot(ly=ly, xs=xs, os_=os_, turn=turn):
                             k = turn[0] % len(xs)
                             turn[0] += 1
-                            ly["L"].conv2d(xs[k], ly["bias"], os_[k], relu=True)
+                            ly["L"].conv2d_ws(xs[k], ly["bias"], os_[k], workspace=ws, relu=True)
                         for _ in range(copies):
                             rot()
                         ms = sorted(timed_ms(rot, max(20, copies)))
@@ -411,7 +417,7 @@ def main() -> int:
         def stack_latency(cfg_no):
             """One image through every layer of a configuration, launches back to back."""
             one = build_stack(cfg_no, 1, per_image_input=False)
-            run = lambda: [ly["L"].conv2d(ly["x"], ly["bias"], ly["out"], relu=True) for ly in one]
+            run = lambda: [ly["L"].conv2d_ws(ly["x"], ly["bias"], ly["out"], workspace=ws, relu=True) for ly in one]
             for _ in range(3):
                 run()
             torch.cuda.synchronize()
@@ -509,7 +515,7 @@ def main() -> int:
             seen_shapes.add(wl.shape_key(spec))
             L = ly["L"]
             tuned_cfg = L.get_config()
-            run = lambda: L.conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+            run = lambda: L.conv2d_ws(ly["x"], ly["bias"], ly["out"], workspace=ws, relu=True)
             ms = {}
             for stage, (vname, ck, waves) in (("noopt", ("noopt", 0, 0)), ("reorder", ("fkw", 0, 0)),
                                               ("lre", ("t_g16_p7x1_s1_x16", 0, 0)), ("csr", ("csr", 0, 0))):
@@ -553,7 +559,7 @@ def main() -> int:
                 ids_k = np.random.default_rng(600 + kpat).integers(0, kpat, d["pattern_ids"].shape, dtype=np.uint8)
                 Lk = B.Layer(d["weights"], ids_k, d["kernel_mask"], lib_k, stride=spec.stride, pad=spec.pad)
                 Lk.set_config(cfg0["variant"], cfg0["ck"], cfg0["waves"], cfg0["ksplit"])
-                runk = lambda: Lk.conv2d(ly["x"], ly["bias"], ly["out"], relu=True)
+                runk = lambda: Lk.conv2d_ws(ly["x"], ly["bias"], ly["out"], workspace=ws, relu=True)
                 runk()
                 ms = sorted(timed_ms(runk, 7))[3]
                 sweep["rows"].append({"layer": spec.name, "patterns": kpat, "ms": round(ms, 4),

@@ -148,6 +148,32 @@ patdnn_status_t patdnn_conv2d_f16(patdnn_handle_t h, const void* input, int32_t 
 patdnn_status_t patdnn_conv2d_pool(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
                                    int32_t w_in, const float* bias, float* output, void* stream);
 
+/*
+ * patdnn_conv2d / patdnn_conv2d_pool with a workspace from the caller, for layers whose
+ * configuration splits the input channels into slices (`ksplit` > 1 of patdnn_config_t: the
+ * way a layer with few output tiles fills the chip; section 5.5 leaves such launch
+ * parameters to the tuner).  Without a workspace the slices add their partial sums into the
+ * zeroed output with atomics (three launches: zero fill, the layer, bias + activation; the order
+ * of the additions, and with it the last bits of the result, varies from run to run).  With
+ * a workspace of patdnn_workspace_floats() floats every slice stores its partial sums to a
+ * buffer of its own and the finishing kernel adds the buffers in slice order: two launches, no
+ * atomics, and results that repeat bit for bit.
+ *   pool2             non-zero: ReLU + 2x2 max pooling fused as in patdnn_conv2d_pool (`fuse_relu`
+ *                     is then implied and `output` is the pooled tensor); a pooled layer
+ *                     keeps its split configuration only with a workspace
+ *   workspace         DEVICE, 16-byte aligned (else PATDNN_EINVAL), caller-owned, contents
+ *                     undefined before and after; may be NULL (then as the plain calls)
+ *   workspace_floats  its size; if it is smaller than the layer needs the call runs as
+ *                     without one
+ * Calls that share a workspace must not overlap in time.  Nothing is allocated.
+ * patdnn_workspace_floats: what the handle's present configuration can use at this input
+ * size (0: it does not split; also 0 for arguments that patdnn_conv2d would reject).
+ */
+size_t patdnn_workspace_floats(patdnn_handle_t h, int32_t n, int32_t h_in, int32_t w_in);
+patdnn_status_t patdnn_conv2d_ws(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in, int32_t w_in,
+                                 const float* bias, float* output, int32_t fuse_relu, int32_t pool2,
+                                 float* workspace, size_t workspace_floats, void* stream);
+
 /* out_nchw = {n, c_out, h_out, w_out}; PATDNN_EINVAL if the output would be empty. */
 patdnn_status_t patdnn_output_shape(patdnn_handle_t h, int32_t n, int32_t h_in, int32_t w_in,
                                     int32_t out_nchw[4]);
@@ -256,6 +282,15 @@ patdnn_status_t patdnn_get_config(patdnn_handle_t h, patdnn_config_t* cfg);
 patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
                             int32_t w_in, const float* bias, float* output, void* stream,
                             float* best_us);
+/*
+ * The same search for callers of patdnn_conv2d_ws: candidates that split the input channels
+ * are timed with the workspace (DEVICE, 16-byte aligned, caller-owned; those it is too small
+ * for are timed as without one), so the configuration kept is the fastest for calls that
+ * pass a workspace of this size.  NULL / 0: exactly patdnn_tune.
+ */
+patdnn_status_t patdnn_tune_ws(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
+                               int32_t w_in, const float* bias, float* output, float* workspace,
+                               size_t workspace_floats, void* stream, float* best_us);
 
 /*
  * The filter-group layout that a tiled sparse variant executes (section 5.2-5.4 as

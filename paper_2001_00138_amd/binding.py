@@ -23,10 +23,11 @@ PATDNN_VARIANT_FKW = 0
 
 EXPORTS = [
     "patdnn_mine_patterns", "patdnn_project_patterns", "patdnn_project_connectivity",
-    "patdnn_encode", "patdnn_conv2d", "patdnn_conv2d_f16", "patdnn_conv2d_pool", "patdnn_output_shape", "patdnn_decode",
+    "patdnn_encode", "patdnn_conv2d", "patdnn_conv2d_f16", "patdnn_conv2d_pool", "patdnn_conv2d_ws", "patdnn_workspace_floats",
+    "patdnn_output_shape", "patdnn_decode",
     "patdnn_stack_create", "patdnn_stack_output_shape", "patdnn_stack_run", "patdnn_stack_run_static", "patdnn_stack_destroy",
     "patdnn_export_fkw", "patdnn_export_csr", "patdnn_layout_stats", "patdnn_num_variants", "patdnn_variant_name",
-    "patdnn_set_config", "patdnn_get_config", "patdnn_tune", "patdnn_tiled_info",
+    "patdnn_set_config", "patdnn_get_config", "patdnn_tune", "patdnn_tune_ws", "patdnn_tiled_info",
     "patdnn_export_tiled", "patdnn_selftest", "patdnn_destroy",
     "patdnn_status_string", "patdnn_last_error",
 ]
@@ -96,6 +97,9 @@ def lib() -> ctypes.CDLL:
         L.patdnn_project_connectivity.argtypes = [vp, i32, i32, ctypes.c_int64, vp]
         L.patdnn_conv2d_f16.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, vp]
         L.patdnn_conv2d_pool.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+        L.patdnn_conv2d_ws.argtypes = [vp, vp, i32, i32, i32, vp, vp, i32, i32, vp, ctypes.c_size_t, vp]
+        L.patdnn_workspace_floats.argtypes = [vp, i32, i32, i32]
+        L.patdnn_workspace_floats.restype = ctypes.c_size_t
         L.patdnn_stack_create.argtypes = [ctypes.POINTER(StackLayer), i32, i32, i32, i32, ctypes.POINTER(vp)]
         L.patdnn_stack_output_shape.argtypes = [vp, ctypes.POINTER(i32 * 4)]
         L.patdnn_stack_run.argtypes = [vp, vp, vp, i32, vp]
@@ -113,6 +117,8 @@ def lib() -> ctypes.CDLL:
         L.patdnn_set_config.argtypes = [vp, ctypes.POINTER(Config)]
         L.patdnn_get_config.argtypes = [vp, ctypes.POINTER(Config)]
         L.patdnn_tune.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_float)]
+        L.patdnn_tune_ws.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, ctypes.c_size_t, vp,
+                                     ctypes.POINTER(ctypes.c_float)]
         L.patdnn_tiled_info.argtypes = [vp, i32, i32, ctypes.POINTER(TiledInfo)]
         L.patdnn_export_tiled.argtypes = [vp, i32, i32, vp, vp, vp]
         L.patdnn_selftest.argtypes = []
@@ -236,6 +242,34 @@ def patdnn_conv2d(handle: int, x, bias=None, out=None, *, fuse_relu=False, strea
         raise ValueError("bias must be float32 [c_out]")
     _check(lib().patdnn_conv2d(handle, _devptr(x), n, h_in, w_in, _devptr(bias), _devptr(out),
                                int(bool(fuse_relu)), _stream_ptr(stream)))
+    return out
+
+
+def patdnn_workspace_floats(handle: int, n: int, h_in: int, w_in: int) -> int:
+    return int(lib().patdnn_workspace_floats(handle, n, h_in, w_in))
+
+
+def patdnn_conv2d_ws(handle: int, x, bias=None, out=None, *, workspace=None, fuse_relu=False, pool=False,
+                     stream=None):
+    """patdnn_conv2d / patdnn_conv2d_pool with a caller-owned workspace (a float32 device tensor)
+    for the partial sums of a configuration that splits the input channels."""
+    import torch
+    if x.dtype != torch.float32 or x.dim() != 4:
+        raise ValueError("input must be a 4-d float32 tensor")
+    n, _, h_in, w_in = x.shape
+    full = patdnn_output_shape(handle, n, h_in, w_in)
+    shape = (full[0], full[1], full[2] // 2, full[3] // 2) if pool else full
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=x.device)
+    elif tuple(out.shape) != shape or out.dtype != torch.float32:
+        raise ValueError(f"output must be float32 {shape}")
+    if bias is not None and (bias.dtype != torch.float32 or bias.numel() != shape[1]):
+        raise ValueError("bias must be float32 [c_out]")
+    if workspace is not None and (workspace.dtype != torch.float32 or not workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous float32 tensor")
+    _check(lib().patdnn_conv2d_ws(handle, _devptr(x), n, h_in, w_in, _devptr(bias), _devptr(out),
+                                  int(bool(fuse_relu)), int(bool(pool)), _devptr(workspace),
+                                  0 if workspace is None else workspace.numel(), _stream_ptr(stream)))
     return out
 
 
@@ -371,12 +405,17 @@ def patdnn_get_config(handle: int) -> dict:
     return {"variant": c.variant, "ck": c.ck, "waves": c.waves, "ksplit": c.ksplit}
 
 
-def patdnn_tune(handle: int, x, bias, out, *, stream=None) -> float:
-    """Times every applicable configuration on the given buffers; returns best microseconds."""
+def patdnn_tune(handle: int, x, bias, out, *, workspace=None, stream=None) -> float:
+    """Times every applicable configuration on the given buffers (split configurations with the
+    workspace, a float32 device tensor, if one is given); returns best microseconds."""
     n, _, h_in, w_in = x.shape
     best = ctypes.c_float()
-    _check(lib().patdnn_tune(handle, _devptr(x), n, h_in, w_in, _devptr(bias), _devptr(out),
-                             _stream_ptr(stream), ctypes.byref(best)))
+    if workspace is None:
+        _check(lib().patdnn_tune(handle, _devptr(x), n, h_in, w_in, _devptr(bias), _devptr(out),
+                                 _stream_ptr(stream), ctypes.byref(best)))
+    else:
+        _check(lib().patdnn_tune_ws(handle, _devptr(x), n, h_in, w_in, _devptr(bias), _devptr(out),
+                                    _devptr(workspace), workspace.numel(), _stream_ptr(stream), ctypes.byref(best)))
     return float(best.value)
 
 
@@ -432,6 +471,13 @@ class Layer:
     def conv2d(self, x, bias=None, out=None, *, relu=False, stream=None):
         return patdnn_conv2d(self.handle, x, bias, out, fuse_relu=relu, stream=stream)
 
+    def conv2d_ws(self, x, bias=None, out=None, *, workspace=None, relu=False, pool=False, stream=None):
+        return patdnn_conv2d_ws(self.handle, x, bias, out, workspace=workspace, fuse_relu=relu, pool=pool,
+                                stream=stream)
+
+    def workspace_floats(self, n, h, w):
+        return patdnn_workspace_floats(self.handle, n, h, w)
+
     def conv2d_f16(self, x, bias=None, out=None, *, relu=False, stream=None):
         return patdnn_conv2d_f16(self.handle, x, bias, out, fuse_relu=relu, stream=stream)
 
@@ -462,8 +508,8 @@ class Layer:
     def export_tiled(self, variant, ck=0):
         return patdnn_export_tiled(self.handle, variant, ck)
 
-    def tune(self, x, bias, out, *, stream=None):
-        return patdnn_tune(self.handle, x, bias, out, stream=stream)
+    def tune(self, x, bias, out, *, workspace=None, stream=None):
+        return patdnn_tune(self.handle, x, bias, out, workspace=workspace, stream=stream)
 
     def close(self):
         patdnn_destroy(self.handle)

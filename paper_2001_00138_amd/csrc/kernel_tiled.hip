@@ -54,6 +54,9 @@ struct TiledArgs {
     // with late_from 0 = the launch is a single round, priority follows the remaining work;
     // late_from INT32_MAX = every wavefront stays at the default priority
     int32_t late_from, late_span;
+    // split launches: 0 = the slices ADD into `out` (zeroed beforehand) with atomics; otherwise
+    // slice y STORES its partial sums to out + y * slice_stride (floats), a buffer of its own
+    size_t slice_stride;
 #ifdef PATDNN_TIMELINE
     unsigned long long* tl;      // [blocks][8 waves][8 phases] cycle totals (debug builds only)
 #endif
@@ -299,9 +302,13 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
         }
         if constexpr (ONE_BUFFER) {
             __syncthreads();                      // everyone has finished reading the buffer
+            TL_MARK(5);                           // barrier
             stage(c0, lds3);
+            TL_MARK(2);                           // issuing the chunk's loads
             __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0)
+            TL_MARK(1);                           // wait for the staged chunk
             __syncthreads();
+            TL_MARK(6);                           // second barrier
         } else {
             // chunk `chunk` has landed in this wavefront's view, and (barrier) in everyone's;
             // everyone has also finished reading the other buffer
@@ -353,7 +360,16 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     }
 
     // ---- epilogue: bias, ReLU, scatter to the original output channel
+    // A split launch either adds its slices up in the output with atomics, or (slice_stride != 0)
+    // gives every slice a buffer of its own, which it fills with the plain stores of the unsplit
+    // epilogue (bias NULL, no activation: the launcher sees to both); a finishing kernel adds the
+    // buffers up in a fixed order.
+    const bool to_slices = SPLITK && a.slice_stride != 0;
+    float* const out_base = SPLITK ? a.out + (size_t)blockIdx.y * a.slice_stride : a.out;
+    bool written = false;
     if constexpr (SPLITK && PC == 2 && 64 % (TGX * PC) == 0) {
+      if (!to_slices) {
+        written = true;
         // Partial sums go out as atomic adds, which run at full rate only on whole runs of
         // consecutive floats: 16 lanes on 16 neighbouring outputs cost next to nothing, the
         // same values written lane by lane (a lane's two outputs of a row are neighbours, so
@@ -401,7 +417,9 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                 }
             }
         }
-    } else if (group_ok && band_ok) {
+      }
+    }
+    if (!written && group_ok && band_ok) {
         const size_t oplane = (size_t)a.ho * a.wo;
         if (!SPLITK && a.pool) {
             // ReLU + 2x2 max pooling: fold every value into its pooled cell (zero beforehand)
@@ -422,7 +440,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                             atomicMax(&dst[(size_t)(oy >> 1) * pwo + (ox >> 1)], __float_as_uint(v));
                     }
             }
-        } else if (!SPLITK && PC == 2 && (a.wo & 1) == 0 && (reinterpret_cast<uintptr_t>(a.out) & 7) == 0) {
+        } else if ((!SPLITK || to_slices) && PC == 2 && (a.wo & 1) == 0 && (reinterpret_cast<uintptr_t>(out_base) & 7) == 0) {
             // a lane's two outputs of a row are neighbours at an even column: with an even row
             // length (and an 8-byte aligned tensor) they go out as one 8-byte store
             struct alignas(8) Pair { float x, y; };
@@ -431,7 +449,7 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                 const int co = load_uniform(a.slot_channel, group * G + s);
                 if (co < 0) continue;
                 const float b = a.bias ? load_uniform(a.bias, co) : 0.0f;
-                float* dst = a.out + ((size_t)img * a.c_out + co) * oplane;
+                float* dst = out_base + ((size_t)img * a.c_out + co) * oplane;
 #pragma unroll
                 for (int r = 0; r < PR; ++r) {
                     const int oy = oy0 + r;
@@ -446,13 +464,13 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
                 const int co = load_uniform(a.slot_channel, group * G + s);
                 if (co < 0) continue;
                 const float b = a.bias ? load_uniform(a.bias, co) : 0.0f;
-                float* dst = a.out + ((size_t)img * a.c_out + co) * oplane;
+                float* dst = out_base + ((size_t)img * a.c_out + co) * oplane;
 #pragma unroll
                 for (int r = 0; r < PR; ++r)
 #pragma unroll
                     for (int c = 0; c < PC; ++c) {
                         const int oy = oy0 + r, ox = ox0 + c;
-                        if constexpr (SPLITK) {
+                        if (SPLITK && !to_slices) {
                             if (oy < a.ho && ox < a.wo) unsafeAtomicAdd(&dst[(size_t)oy * a.wo + ox], acc[s][r * PC + c]);
                         } else {
                             float v = acc[s][r * PC + c] + b;
@@ -481,7 +499,9 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(float* p, size_t n)
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0.0f;
 }
 
-// out[n][c][pixel] = act(out + bias[c]) in place, after the split kernels have added up.
+// out[n][c][pixel] = act(sum + bias[c]) after a split launch: `sum` is the output itself (the
+// slices were added up in place with atomics; slices == 1) or `slices` buffers of partial sums,
+// slice_stride floats apart, added here in the order of the slices.
 // A unit is VEC floats of one plane (VEC = 4 where planes are whole aligned float4s); which
 // channel a unit belongs to comes from multiplications where the count allows (a 64-bit
 // division per element would cost more than the memory traffic of a small layer).
@@ -491,6 +511,9 @@ struct FinishArgs {
     size_t plane_units, total_units;
     FastDiv div_plane, div_c;            // used when total_units < 2^31
     int c_out, relu;
+    const float* sums;                   // first buffer of partial sums (== out when added in place)
+    size_t slice_stride;                 // floats between the buffers
+    int slices;
 };
 
 template <int VEC>
@@ -512,23 +535,59 @@ __global__ __launch_bounds__(256) void bias_act_kernel(float* out, const float* 
             b = bias[c];
         }
         if constexpr (VEC == 4) {
-            float4 v = reinterpret_cast<float4*>(out)[u];
+            // up to eight buffers' loads in flight at a time (a single image splits into up to 32
+            // slices; one load after the other would cost their latencies in a row); the
+            // additions stay in slice order
+            auto part = [&](int k) { return reinterpret_cast<const float4*>(a.sums + (size_t)k * a.slice_stride)[u]; };
+            float4 v = part(0);
+            int k = 1;
+            for (; k + 7 < a.slices; k += 8) {
+                float4 t[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) t[j] = part(k + j);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) { v.x += t[j].x; v.y += t[j].y; v.z += t[j].z; v.w += t[j].w; }
+            }
+            for (; k + 3 < a.slices; k += 4) {
+                const float4 t0 = part(k), t1 = part(k + 1), t2 = part(k + 2), t3 = part(k + 3);
+                v.x += t0.x; v.y += t0.y; v.z += t0.z; v.w += t0.w;
+                v.x += t1.x; v.y += t1.y; v.z += t1.z; v.w += t1.w;
+                v.x += t2.x; v.y += t2.y; v.z += t2.z; v.w += t2.w;
+                v.x += t3.x; v.y += t3.y; v.z += t3.z; v.w += t3.w;
+            }
+            for (; k < a.slices; ++k) {
+                const float4 t = part(k);
+                v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+            }
             v.x += b; v.y += b; v.z += b; v.w += b;
             if (a.relu) { v.x = fmaxf(v.x, 0.0f); v.y = fmaxf(v.y, 0.0f); v.z = fmaxf(v.z, 0.0f); v.w = fmaxf(v.w, 0.0f); }
             reinterpret_cast<float4*>(out)[u] = v;
         } else {
-            float v = out[u] + b;
+            float v = a.sums[u];
+            int k = 1;
+            for (; k + 3 < a.slices; k += 4) {
+                const float t0 = a.sums[(size_t)k * a.slice_stride + u], t1 = a.sums[(size_t)(k + 1) * a.slice_stride + u];
+                const float t2 = a.sums[(size_t)(k + 2) * a.slice_stride + u], t3 = a.sums[(size_t)(k + 3) * a.slice_stride + u];
+                v += t0; v += t1; v += t2; v += t3;
+            }
+            for (; k < a.slices; ++k) v += a.sums[(size_t)k * a.slice_stride + u];
+            v += b;
             if (a.relu) v = fmaxf(v, 0.0f);
             out[u] = v;
         }
     }
 }
 
-static void launch_bias_act(float* out, const float* bias, int c_out, size_t plane, size_t total, int relu,
-                            float* zero, size_t zero_count, hipStream_t stream)
+static void launch_bias_act(float* out, const float* sums, int slices, size_t slice_stride, const float* bias,
+                            int c_out, size_t plane, size_t total, int relu, float* zero, size_t zero_count,
+                            hipStream_t stream)
 {
-    const bool vec = plane % 4 == 0 && (reinterpret_cast<uintptr_t>(out) & 15) == 0;
+    const bool vec = plane % 4 == 0 && ((reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(sums)) & 15) == 0 &&
+                     slice_stride % 4 == 0;
     FinishArgs a{};
+    a.sums = sums;
+    a.slices = slices;
+    a.slice_stride = slice_stride;
     a.zero = zero;
     a.zero_count = zero ? zero_count : 0;
     a.plane_units = vec ? plane / 4 : plane;
@@ -558,11 +617,13 @@ static hipError_t allow_big_lds(const void* fn, std::atomic<uint64_t>& done)
 }
 
 // out[n][c][py][px] = max over the 2x2 window of relu(sum[n][c][2py+dy][2px+dx] + bias[c]):
-// finishes a split-channel launch whose partial sums were added up in `sum`
+// finishes a split-channel launch whose partial sums were added up in `sum` (slices == 1) or
+// lie in `slices` buffers, slice_stride floats apart, from `sum` on
 __global__ __launch_bounds__(256) void bias_relu_pool_kernel(const float* sum, const float* bias, float* out,
                                                              int c_out, int ho, int wo, int pho, int pwo, size_t total,
                                                              FastDiv div_pwo, FastDiv div_pho, FastDiv div_c,
-                                                             float* zero, size_t zero_count)
+                                                             float* zero, size_t zero_count, int slices,
+                                                             size_t slice_stride)
 {
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     const bool small = total <= 0x7FFFFFFFull;      // then the divisions are multiplications
@@ -587,7 +648,12 @@ __global__ __launch_bounds__(256) void bias_relu_pool_kernel(const float* sum, c
         }
         const float b = bias ? bias[c] : 0.0f;
         const float* src = sum + (r * ho + 2 * py) * (size_t)wo + 2 * px;
-        const float m = fmaxf(fmaxf(src[0], src[1]), fmaxf(src[wo], src[wo + 1]));
+        float v00 = src[0], v01 = src[1], v10 = src[wo], v11 = src[wo + 1];
+        for (int k = 1; k < slices; ++k) {           // buffers of partial sums, in slice order
+            const float* t = src + (size_t)k * slice_stride;
+            v00 += t[0]; v01 += t[1]; v10 += t[wo]; v11 += t[wo + 1];
+        }
+        const float m = fmaxf(fmaxf(v00, v01), fmaxf(v10, v11));
         out[i] = fmaxf(m + b, 0.0f);
     }
 }
@@ -627,7 +693,7 @@ static bool wave_priority_enabled()
 template <class GEO>
 static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const float* in,
                                const float* bias, float* out, int32_t waves, int32_t ksplit,
-                               float* scratch, hipStream_t stream)
+                               float* scratch, size_t scratch_floats, hipStream_t stream)
 {
     TiledArgs a{};
     a.in = in; a.bias = bias; a.out = out;
@@ -695,10 +761,19 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
         set_priorities(reinterpret_cast<const void*>(&tiled_conv_kernel<GEO, true>), blocks * ksplit);
         const size_t plane = (size_t)s.ho * s.wo, total = (size_t)s.n * s.c_out * plane;
         const unsigned fill_blocks = (unsigned)std::min<size_t>((total + 255) / 256, 256 * 32);
-        float* sums = s.pool ? scratch : out;
+        // With room for one buffer per slice the slices store their partial sums (no zero fill,
+        // no atomics, and a sum in a fixed order: results repeat bit for bit); otherwise they add
+        // into the output - or, for a pooled layer, into the one buffer there is room for.
+        const size_t slice_stride = split_slice_stride(total);
+        const bool to_slices = scratch && scratch_floats / (size_t)ksplit >= slice_stride &&
+                               (reinterpret_cast<uintptr_t>(scratch) & 15) == 0;
+        if (s.pool && !to_slices && scratch_floats < total) return hipErrorInvalidValue;
+        float* sums = (s.pool || to_slices) ? scratch : out;
         a.out = sums;
-        a.pool = 0;                                  // the slices add plain partial sums
-        if (!(s.pre_zeroed == sums && s.pre_zeroed_count >= total))
+        a.pool = 0;                                  // the slices write plain partial sums
+        a.slice_stride = to_slices ? slice_stride : 0;
+        if (to_slices) { a.bias = nullptr; a.relu = 0; }
+        if (!to_slices && !(s.pre_zeroed == sums && s.pre_zeroed_count >= total))
             hipLaunchKernelGGL(fill_zero_kernel, dim3(fill_blocks), dim3(256), 0, stream, sums, total);
         // the finishing kernel below may clear the next launch's target on the way, unless that
         // is the very buffer it reads the sums from
@@ -715,9 +790,11 @@ static hipError_t launch_tiled(const DevTiled& t, const ConvShape& s, const floa
             hipLaunchKernelGGL(bias_relu_pool_kernel, dim3(pblocks), dim3(256), 0, stream,
                                static_cast<const float*>(sums), bias, out, s.c_out, s.ho, s.wo, pho, pwo, ptotal,
                                make_fast_div((uint32_t)std::max(pwo, 1)), make_fast_div((uint32_t)std::max(pho, 1)),
-                               make_fast_div((uint32_t)s.c_out), zero_next, zero_next_count);
+                               make_fast_div((uint32_t)s.c_out), zero_next, zero_next_count,
+                               to_slices ? ksplit : 1, slice_stride);
         } else {
-            launch_bias_act(out, bias, s.c_out, plane, total, s.relu, zero_next, zero_next_count, stream);
+            launch_bias_act(out, sums, to_slices ? ksplit : 1, slice_stride, bias, s.c_out, plane, total, s.relu,
+                            zero_next, zero_next_count, stream);
         }
         return hipGetLastError();
     }
@@ -742,6 +819,8 @@ static const TiledVariant kVariants[] = {
     PATDNN_VARIANTS
 #undef X
 };
+
+size_t split_slice_stride(size_t total) { return (total + 63) / 64 * 64; }
 
 hipError_t launch_fill_zero(float* p, size_t count, hipStream_t stream)
 {

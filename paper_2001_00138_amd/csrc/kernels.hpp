@@ -36,6 +36,10 @@ struct ConvShape {
 // Fills `count` floats with zero (a kernel, so that it can be captured into a HIP graph).
 hipError_t launch_fill_zero(float* p, size_t count, hipStream_t stream);
 
+// Floats between the partial-sum buffers of a split launch whose output has `total` floats (a
+// launch with `ksplit` slices stores to buffers if its scratch holds ksplit of them).
+size_t split_slice_stride(size_t total);
+
 // Division of a value below 2^31 by a launch-time constant d >= 1 without the divider loop:
 // with l = ceil(log2 d) and m = ceil(2^(31+l) / d) (which fits 32 bits), floor(n / d) =
 // (n * m) >> (31 + l) exactly for every n < 2^31 (the error term n * (m*d - 2^(31+l)) /
@@ -138,11 +142,14 @@ struct TiledVariant {
     uint32_t table_off;               // offset of block 0 from the code base
     uint32_t ctrl_bytes;              // control block k sits at k*ctrl_bytes
     uint32_t records;                 // kernels per step
-    // ksplit > 1 (sparse variants): slices of the input channels on gridDim.y, summed with atomics.
-    // With fused pooling the slices are summed in `scratch` ([n][c_out][ho][wo] floats, DEVICE)
-    // and a finishing kernel writes the pooled output; otherwise `scratch` is not used.
+    // ksplit > 1 (sparse variants): slices of the input channels on gridDim.y.  `scratch` (DEVICE,
+    // 16-byte aligned, `scratch_floats` floats, may be NULL): with room for ksplit buffers of
+    // split_slice_stride([n][c_out][ho][wo]) floats every slice stores its partial sums to its
+    // own buffer and a finishing kernel adds them up; otherwise the slices are summed with
+    // atomics, in the output or - with fused pooling, which then needs [n][c_out][ho][wo]
+    // floats of scratch - in `scratch`, and a finishing kernel writes the pooled output.
     hipError_t (*launch)(const DevTiled&, const ConvShape&, const float*, const float*, float*,
-                         int32_t waves, int32_t ksplit, float* scratch, hipStream_t);
+                         int32_t waves, int32_t ksplit, float* scratch, size_t scratch_floats, hipStream_t);
 };
 
 // Device check that s_movrels_b32 / _b64 behave as the threaded interpreter assumes.

@@ -284,7 +284,7 @@ patdnn_status_t shape_of(const patdnn_layer* h, int32_t n, int32_t h_in, int32_t
 // Launch with an explicit configuration (variant >= 0).
 patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const ConvShape& s,
                            const float* in, const float* bias, float* out, hipStream_t stream,
-                           float* scratch = nullptr)
+                           float* scratch = nullptr, size_t scratch_floats = 0)
 {
     if (c.variant == PATDNN_VARIANT_FKW) {
         hipError_t e = launch_fkw(h->dfkw, s, in, bias, out, stream);
@@ -321,7 +321,7 @@ patdnn_status_t run_config(patdnn_layer* h, const patdnn_config_t& c, const Conv
     DevTiled dt = *t;
     if (v.dense) { dt.ck = ck; dt.num_chunks = (s.c_in + ck - 1) / ck; }
     if (c.ksplit > dt.num_chunks) return fail(PATDNN_EUNSUPPORTED, "ksplit exceeds the number of channel chunks");
-    hipError_t e = v.launch(dt, s, in, bias, out, waves, c.ksplit, scratch, stream);
+    hipError_t e = v.launch(dt, s, in, bias, out, waves, c.ksplit, scratch, scratch_floats, stream);
     return e == hipSuccess ? PATDNN_OK : hip_fail(e, "launching a tiled kernel");
 }
 
@@ -465,6 +465,14 @@ struct ZeroHandoff {
     bool done = false;       // out: `next` was cleared by this layer
 };
 
+// A split launch stores its slices to buffers of their own (no zero fill, no atomics) if the
+// scratch holds one per slice; the launcher decides by the same rule.
+static bool slices_fit(const float* scratch, size_t scratch_floats, int32_t ksplit, size_t full)
+{
+    return scratch && ksplit > 1 && (reinterpret_cast<uintptr_t>(scratch) & 15) == 0 &&
+           scratch_floats / (size_t)ksplit >= split_slice_stride(full);
+}
+
 // The region that conv2d_impl must clear before this layer's kernels run (none: p == NULL).
 // Mirrors the decisions of conv2d_impl below.
 static ZeroRegion zero_need(patdnn_handle_t h, int32_t n, int32_t h_in, int32_t w_in, int32_t pool, float* output,
@@ -475,13 +483,16 @@ static ZeroRegion zero_need(patdnn_handle_t h, int32_t n, int32_t h_in, int32_t 
     const patdnn_config_t& c = h->cfg;
     const bool split = c.variant > 0 && c.ksplit > 1;
     const size_t full = (size_t)n * s.c_out * s.ho * s.wo;
+    if (split && slices_fit(scratch, scratch_floats, c.ksplit, full)) return ZeroRegion{};   // stores only
     if (!pool) return split ? ZeroRegion{output, full} : ZeroRegion{};
     if (split && scratch && scratch_floats >= full) return ZeroRegion{scratch, full};
     return ZeroRegion{output, (size_t)n * s.c_out * (s.ho / 2) * (s.wo / 2)};
 }
 
-// `scratch` (DEVICE, `scratch_floats` floats, may be NULL): where a pooled layer whose
-// configuration splits the input channels adds up its partial sums ([n][c_out][ho][wo]).
+// `scratch` (DEVICE, `scratch_floats` floats, may be NULL): where a layer whose configuration
+// splits the input channels keeps its partial sums: one buffer per slice if there is room
+// (ksplit * split_slice_stride([n][c_out][ho][wo]) floats), else - pooled layers only - one
+// buffer that the slices add into ([n][c_out][ho][wo]).
 static patdnn_status_t conv2d_impl(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
                                    int32_t w_in, const float* bias, float* output, int32_t fuse_relu,
                                    int32_t pool, hipStream_t stream, float* scratch = nullptr,
@@ -523,7 +534,7 @@ static patdnn_status_t conv2d_impl(patdnn_handle_t h, const float* input, int32_
         hipError_t e = launch_fill_zero(output, (size_t)n * s.c_out * oh * ow, stream);
         if (e != hipSuccess) return hip_fail(e, "zeroing the pooled output");
     }
-    st = run_config(h, c, s, input, bias, output, stream, scratch);
+    st = run_config(h, c, s, input, bias, output, stream, scratch, scratch_floats);
     if (st == PATDNN_EUNSUPPORTED && h->cfg.variant > 0 && h->cfg_tuned) {
         // a configuration tuned for another input size may not fit this one; a configuration
         // the caller set explicitly is never replaced: the error goes back instead
@@ -532,7 +543,7 @@ static patdnn_status_t conv2d_impl(patdnn_handle_t h, const float* input, int32_
             hipError_t e = launch_fill_zero(output, (size_t)n * s.c_out * oh * ow, stream);
             if (e != hipSuccess) return hip_fail(e, "zeroing the pooled output");
         }
-        st = run_config(h, c, s, input, bias, output, stream, scratch);
+        st = run_config(h, c, s, input, bias, output, stream, scratch, scratch_floats);
     }
     return st;
 }
@@ -542,6 +553,25 @@ patdnn_status_t patdnn_conv2d(patdnn_handle_t h, const float* input, int32_t n, 
                               void* stream)
 {
     return conv2d_impl(h, input, n, h_in, w_in, bias, output, fuse_relu, 0, static_cast<hipStream_t>(stream));
+}
+
+size_t patdnn_workspace_floats(patdnn_handle_t h, int32_t n, int32_t h_in, int32_t w_in)
+{
+    ConvShape s{};
+    if (shape_of(h, n, h_in, w_in, s) != PATDNN_OK) return 0;
+    const patdnn_config_t& c = h->cfg;
+    if (!(c.variant > 0 && c.ksplit > 1)) return 0;
+    return (size_t)c.ksplit * split_slice_stride((size_t)n * s.c_out * s.ho * s.wo);
+}
+
+patdnn_status_t patdnn_conv2d_ws(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in, int32_t w_in,
+                                 const float* bias, float* output, int32_t fuse_relu, int32_t pool2,
+                                 float* workspace, size_t workspace_floats, void* stream)
+{
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 15))
+        return fail(PATDNN_EINVAL, "workspace must be 16-byte aligned");
+    return conv2d_impl(h, input, n, h_in, w_in, bias, output, pool2 ? 1 : fuse_relu, pool2 ? 1 : 0,
+                       static_cast<hipStream_t>(stream), workspace, workspace ? workspace_floats : 0);
 }
 
 patdnn_status_t patdnn_conv2d_f16(patdnn_handle_t h, const void* input, int32_t n, int32_t h_in, int32_t w_in,
@@ -773,6 +803,16 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
                             int32_t w_in, const float* bias, float* output, void* stream_,
                             float* best_us)
 {
+    return patdnn_tune_ws(h, input, n, h_in, w_in, bias, output, nullptr, 0, stream_, best_us);
+}
+
+patdnn_status_t patdnn_tune_ws(patdnn_handle_t h, const float* input, int32_t n, int32_t h_in,
+                               int32_t w_in, const float* bias, float* output, float* workspace,
+                               size_t workspace_floats, void* stream_, float* best_us)
+{
+    if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 15))
+        return fail(PATDNN_EINVAL, "workspace must be 16-byte aligned");
+    if (!workspace) workspace_floats = 0;
     ConvShape s{};
     patdnn_status_t st = shape_of(h, n, h_in, w_in, s);
     if (st != PATDNN_OK) return st;
@@ -825,10 +865,11 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
     patdnn_status_t result = PATDNN_OK;
     // milliseconds per run of one candidate: one warm-up, then `reps` runs between two events
     auto time_config = [&](const patdnn_config_t& c, int reps, float& ms) -> patdnn_status_t {
-        patdnn_status_t r = run_config(h, c, s, input, bias, output, stream);
+        patdnn_status_t r = run_config(h, c, s, input, bias, output, stream, workspace, workspace_floats);
         if (r != PATDNN_OK) return r;
         (void)hipEventRecord(e0, stream);
-        for (int k = 0; k < reps && r == PATDNN_OK; ++k) r = run_config(h, c, s, input, bias, output, stream);
+        for (int k = 0; k < reps && r == PATDNN_OK; ++k)
+            r = run_config(h, c, s, input, bias, output, stream, workspace, workspace_floats);
         (void)hipEventRecord(e1, stream);
         if (r != PATDNN_OK) return r;
         hipError_t he = hipEventSynchronize(e1);
@@ -871,7 +912,7 @@ patdnn_status_t patdnn_tune(patdnn_handle_t h, const float* input, int32_t n, in
     (void)hipEventDestroy(e1);
     if (result != PATDNN_OK) return result;
     // leave a valid result of the chosen configuration in `output`
-    st = run_config(h, best_cfg, s, input, bias, output, stream);
+    st = run_config(h, best_cfg, s, input, bias, output, stream, workspace, workspace_floats);
     if (st != PATDNN_OK) return st;
     if ((e = hipStreamSynchronize(stream)) != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
     h->cfg = best_cfg;
@@ -983,7 +1024,8 @@ struct patdnn_stack {
     int32_t out_shape[4] = {0, 0, 0, 0};
     size_t max_intermediate = 0;              // floats of the largest tensor between two layers
     size_t buf_floats[2] = {0, 0};            // floats the tensors written to buffer 0 / 1 need
-    size_t split_floats = 0;                  // largest un-pooled output of a pooled layer (partial sums)
+    size_t split_floats_min = 0;              // largest un-pooled output of a pooled layer (partial sums)
+    size_t split_floats = 0;                  // >= split_floats_min: room for one buffer per channel slice
     float* buf[2] = {nullptr, nullptr};       // the stack's own ping-pong buffers
     float* split = nullptr;                   // and its buffer for the partial sums of split pooled layers
     hipGraph_t graph = nullptr;
@@ -1004,9 +1046,13 @@ struct patdnn_stack {
 
 namespace {
 
+// A stack gives its split layers one partial-sum buffer per channel slice up to this size
+// (512 MB); a layer that would need more adds its slices up with atomics instead.
+constexpr size_t kMaxSliceFloats = (size_t)128 << 20;
+
 // every layer on `stream`, intermediates alternating between b0 and b1
 patdnn_status_t stack_launch(patdnn_stack* s, const float* input, float* output, float* b0, float* b1,
-                             float* split, hipStream_t stream)
+                             float* split, size_t split_floats, hipStream_t stream)
 {
     const int L = (int)s->layers.size();
     auto dst_of = [&](int i) { return i == L - 1 ? output : ((i & 1) ? b1 : b0); };
@@ -1025,11 +1071,11 @@ patdnn_status_t stack_launch(patdnn_stack* s, const float* input, float* output,
         if (i + 1 < L) {
             const patdnn_stack_layer_t& nx = s->layers[i + 1];
             hand.next = zero_need(nx.layer, s->n, s->in_h[i + 1], s->in_w[i + 1], nx.pool2, dst_of(i + 1), split,
-                                  s->split_floats);
+                                  split_floats);
             if (hand.next.p == dst) hand.next = ZeroRegion{};     // this layer's own output: cannot happen
         }
         patdnn_status_t st = conv2d_impl(ly.layer, src, s->n, s->in_h[i], s->in_w[i], ly.bias, dst, ly.fuse_relu,
-                                         ly.pool2, stream, split, s->split_floats, &hand);
+                                         ly.pool2, stream, split, split_floats, &hand);
         if (st != PATDNN_OK) return st;
         zeroed = hand.done ? hand.next : ZeroRegion{};
         src = dst;
@@ -1065,7 +1111,15 @@ patdnn_status_t patdnn_stack_create(const patdnn_stack_layer_t* layers, int32_t 
         w = ly.pool2 ? cs.wo / 2 : cs.wo;
         if (h <= 0 || w <= 0) return fail(PATDNN_EINVAL, "a layer's output is empty");
         c = cs.c_out;
-        if (ly.pool2) s->split_floats = std::max(s->split_floats, (size_t)n * c * cs.ho * cs.wo);
+        const size_t full = (size_t)n * c * cs.ho * cs.wo;
+        if (ly.pool2) s->split_floats_min = std::max(s->split_floats_min, full);
+        // one buffer per channel slice for the layers that are configured to split now (a layer
+        // reconfigured later uses the room there is, or adds its slices up with atomics)
+        const patdnn_config_t& cfg = ly.layer->cfg;
+        if (cfg.variant > 0 && cfg.ksplit > 1) {
+            const size_t want = (size_t)cfg.ksplit * split_slice_stride(full);
+            if (want <= kMaxSliceFloats) s->split_floats = std::max(s->split_floats, want);
+        }
         if (i + 1 < num_layers) {
             s->max_intermediate = std::max(s->max_intermediate, (size_t)n * c * h * w);
             s->buf_floats[i & 1] = std::max(s->buf_floats[i & 1], (size_t)n * c * h * w);
@@ -1073,6 +1127,7 @@ patdnn_status_t patdnn_stack_create(const patdnn_stack_layer_t* layers, int32_t 
         s->layers.push_back(ly);
     }
     s->out_shape[0] = n; s->out_shape[1] = c; s->out_shape[2] = h; s->out_shape[3] = w;
+    s->split_floats = std::max(s->split_floats, s->split_floats_min);
     for (int k = 0; k < 2; ++k)
         if (s->buf_floats[k]) {
             hipError_t e = hipMalloc(reinterpret_cast<void**>(&s->buf[k]), s->buf_floats[k] * sizeof(float));
@@ -1100,7 +1155,7 @@ patdnn_status_t patdnn_stack_run(patdnn_stack_t s, const float* input, float* ou
     if (!input || !output) return fail(PATDNN_EINVAL, "input / output is NULL");
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (!use_graph) {
-        patdnn_status_t st = stack_launch(s, input, output, s->buf[0], s->buf[1], s->split, stream);
+        patdnn_status_t st = stack_launch(s, input, output, s->buf[0], s->buf[1], s->split, s->split_floats, stream);
         if (st == PATDNN_OK) s->warmed = true;
         return st;
     }
@@ -1109,7 +1164,7 @@ patdnn_status_t patdnn_stack_run(patdnn_stack_t s, const float* input, float* ou
         // (re)capture: the graph holds the tensor addresses it was recorded with
         if (!s->warmed) {
             // a first plain run sets the per-kernel attributes, which must not happen in a capture
-            patdnn_status_t st = stack_launch(s, input, output, s->buf[0], s->buf[1], s->split, stream);
+            patdnn_status_t st = stack_launch(s, input, output, s->buf[0], s->buf[1], s->split, s->split_floats, stream);
             if (st != PATDNN_OK) return st;
             s->warmed = true;
         }
@@ -1117,7 +1172,7 @@ patdnn_status_t patdnn_stack_run(patdnn_stack_t s, const float* input, float* ou
         if (s->graph) { (void)hipGraphDestroy(s->graph); s->graph = nullptr; }
         hipError_t e = hipStreamBeginCapture(stream, hipStreamCaptureModeThreadLocal);
         if (e != hipSuccess) return hip_fail(e, "hipStreamBeginCapture");
-        patdnn_status_t st = stack_launch(s, input, output, s->buf[0], s->buf[1], s->split, stream);
+        patdnn_status_t st = stack_launch(s, input, output, s->buf[0], s->buf[1], s->split, s->split_floats, stream);
         e = hipStreamEndCapture(stream, &s->graph);
         if (st != PATDNN_OK) {
             if (s->graph) { (void)hipGraphDestroy(s->graph); s->graph = nullptr; }
@@ -1182,7 +1237,11 @@ patdnn_status_t patdnn_stack_run_static(patdnn_stack_t s, const float* input, fl
     if (!s) return fail(PATDNN_EINVAL, "stack is NULL");
     if (!input || !output) return fail(PATDNN_EINVAL, "input / output is NULL");
     const size_t b0 = round256(s->buf_floats[0] * sizeof(float)), b1 = round256(s->buf_floats[1] * sizeof(float));
-    const size_t sp = round256(s->split_floats * sizeof(float));
+    // room for one partial-sum buffer per channel slice if the built-in buffer has it, else
+    // the one buffer that split pooled layers cannot do without
+    size_t sp_floats = s->split_floats;
+    if (b0 + b1 + round256(sp_floats * sizeof(float)) > kStaticScratchBytes) sp_floats = s->split_floats_min;
+    const size_t sp = round256(sp_floats * sizeof(float));
     if (b0 + b1 + sp > kStaticScratchBytes) {
         char msg[200];
         snprintf(msg, sizeof(msg), "the stack needs %zu bytes between its layers; the built-in buffer of "
@@ -1195,7 +1254,7 @@ patdnn_status_t patdnn_stack_run_static(patdnn_stack_t s, const float* input, fl
     // nothing here needs to start at zero: the kernels clear the pooled outputs and partial
     // sums they accumulate into, whatever an earlier call left behind
     return stack_launch(s, input, output, reinterpret_cast<float*>(base), reinterpret_cast<float*>(base + b0),
-                        reinterpret_cast<float*>(base + b0 + b1), static_cast<hipStream_t>(stream));
+                        reinterpret_cast<float*>(base + b0 + b1), sp_floats, static_cast<hipStream_t>(stream));
 }
 
 const char* patdnn_status_string(patdnn_status_t s)

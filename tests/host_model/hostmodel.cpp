@@ -123,7 +123,8 @@ extern "C" {
 long hostmodel_run(int variant, int G, int num_groups, int ck, int num_chunks, const int32_t* slot_channel,
                    const uint32_t* chunk_ptr, const uint32_t* steps, const float* w9, int n, int c_in, int c_out,
                    int h, int w, int ho, int wo, int stride, int pad, int relu, const float* in,
-                   const float* bias, float* out, int waves, int ksplit, char* msg, int msg_len)
+                   const float* bias, float* out, int waves, int ksplit, float* scratch, size_t scratch_floats,
+                   char* msg, int msg_len)
 {
     using namespace patdnn;
     hostmodel::State& st = hostmodel::state();
@@ -138,7 +139,7 @@ long hostmodel_run(int variant, int G, int num_groups, int ck, int num_chunks, c
     t.G = G; t.num_groups = num_groups; t.ck = ck; t.num_chunks = num_chunks;
     t.slot_channel = slot_channel; t.chunk_ptr = chunk_ptr; t.steps = steps; t.w9 = w9;
     ConvShape s{n, c_in, c_out, h, w, ho, wo, stride, pad, relu};
-    const hipError_t e = tiled_variant(variant).launch(t, s, in, bias, out, waves, ksplit, nullptr, nullptr);
+    const hipError_t e = tiled_variant(variant).launch(t, s, in, bias, out, waves, ksplit, scratch, scratch_floats, nullptr);
     if (e != hipSuccess) hostmodel::fail("launch refused", e);
     if (msg && msg_len > 0) {
         std::strncpy(msg, st.first_error.c_str(), (size_t)msg_len - 1);

@@ -252,8 +252,15 @@ def test_full_size_sampled(torch, oracle, layer):
     else:
         L.tune(xt, bt, out)
     _say(f"    configuration: {L.get_config()} {B.patdnn_variant_name(L.get_config()['variant'])}")
-    L.conv2d(xt, bt, out, relu=True)
+    # as bench.py launches it: with a workspace for the partial sums of a split configuration
+    # (NaN beforehand and guarded: nothing may be read before it is written, or written outside)
+    need, guard = L.workspace_floats(spec.n, spec.h, spec.w), 4096
+    wbuf = torch.full((need + 2 * guard,), float("nan"), dtype=torch.float32, device="cuda")
+    wbuf[:guard] = 4242.0
+    wbuf[guard + need:] = 4242.0
+    L.conv2d_ws(xt, bt, out, workspace=wbuf[guard:guard + need] if need else None, relu=True)
     torch.cuda.synchronize()
+    assert bool((wbuf[:guard] == 4242.0).all()) and bool((wbuf[guard + need:] == 4242.0).all())
     got = out.cpu().numpy()
     rng = np.random.default_rng(500 + layer)
     coords = np.stack([rng.integers(0, s, 4096) for s in got.shape], axis=1).astype(np.int32)

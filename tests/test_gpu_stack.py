@@ -178,3 +178,46 @@ def test_neighbouring_layers_share_zero_fills(torch, oracle, ksplits):
     st.close()
     for L in Ls:
         L.close()
+
+
+@pytest.mark.parametrize("ksplit", [2, 3])
+def test_pooled_split_layer_with_a_workspace(torch, oracle, ksplit):
+    """patdnn_conv2d_ws with fused pooling on a configuration that splits the input channels:
+    with room for one buffer per slice (stores, summed in slice order: repeatable bits), with
+    room for a single buffer (the slices add into it with atomics), and with none (the call
+    falls back to the layer's default configuration) - all three against the oracle."""
+    from oracle import stack as ostack
+    rng = np.random.default_rng(77 + ksplit)
+    lib = wl.pattern_library(wl.PATTERN_SEED)
+    c_out, c_in, n, h, w = 40, 36, 3, 17, 22
+    ids = rng.integers(0, 8, (c_out, c_in), dtype=np.uint8)
+    mask = (rng.random((c_out, c_in)) < 0.4).astype(np.uint8)
+    wt = rng.standard_normal((c_out, c_in, 3, 3)).astype(np.float32)
+    bias = rng.standard_normal(c_out).astype(np.float32)
+    x = rng.standard_normal((n, c_in, h, w)).astype(np.float32)
+    ref = ostack.maxpool2x2(oracle.conv2d(wt, ids, mask, lib, x, bias, relu=True, skip_removed=True))
+    names = {B.patdnn_variant_name(v): v for v in range(B.patdnn_num_variants())}
+    L = B.Layer(wt, ids, mask, lib)
+    xt, bt = torch.from_numpy(x).cuda(), torch.from_numpy(bias).cuda()
+    for vname in ("t_g8_p7x2_s1_x8_thw1b", "t_g16_p7x1_s1_x16"):
+        L.set_config(names[vname], 8, 4, ksplit)
+        need = L.workspace_floats(n, h, w)
+        full = n * c_out * h * w
+        assert need >= ksplit * full
+        guard = 1024
+        for room, what in ((need, "one buffer per slice"), (full, "one buffer"), (0, "no workspace")):
+            wbuf = torch.full((room + 2 * guard,), float("nan"), dtype=torch.float32, device="cuda")
+            wbuf[:guard] = 4242.0
+            wbuf[guard + room:] = 4242.0
+            outs = []
+            for _ in range(2):
+                out = L.conv2d_ws(xt, bt, workspace=wbuf[guard:guard + room] if room else None, pool=True)
+                torch.cuda.synchronize()
+                assert bool((wbuf[:guard] == 4242.0).all()) and bool((wbuf[guard + room:] == 4242.0).all())
+                err = _rel(out.cpu().numpy(), ref)
+                assert err <= TOL, (vname, what, err)
+                outs.append(out)
+            _say(f"    {vname} ksplit {ksplit}, {what}: rel_err={err:.2e}")
+            if room == need:
+                assert bool((outs[0] == outs[1]).all()), "slice buffers must give repeatable bits"
+    L.close()

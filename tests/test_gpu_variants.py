@@ -79,6 +79,32 @@ def test_every_variant_and_ksplit_matches_the_oracle(torch, oracle, case):
                 _say(f"    rel_err={err:.2e}")
                 assert err <= TOL, (B.patdnn_variant_name(v), ksplit, err)
                 seen += 1
+                need = L.workspace_floats(case["n"], case["h"], case["w"])
+                assert (need > 0) == (L.get_config()["ksplit"] > 1)     # the comparison kernels never split
+                if need:
+                    # the same configuration with one partial-sum buffer per slice: the room is
+                    # NaN beforehand and guarded, and two runs must agree bit for bit (no atomics)
+                    wbuf = torch.full((need + 2 * guard,), float("nan"), dtype=torch.float32, device="cuda")
+                    wbuf[:guard] = 4242.0
+                    wbuf[guard + need:] = 4242.0
+                    runs = []
+                    for _ in range(2):
+                        buf.fill_(12345.0)
+                        L.conv2d_ws(xt, bt, out, workspace=wbuf[guard:guard + need], relu=True)
+                        torch.cuda.synchronize()
+                        assert bool((buf[:guard] == 12345.0).all()) and bool((buf[guard + numel:] == 12345.0).all())
+                        assert bool((wbuf[:guard] == 4242.0).all()) and bool((wbuf[guard + need:] == 4242.0).all())
+                        runs.append(out.clone())
+                    assert bool((runs[0] == runs[1]).all()), "slice buffers must give repeatable bits"
+                    err = float(np.abs(runs[0].cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max())
+                    _say(f"    with a workspace: rel_err={err:.2e}")
+                    assert err <= TOL, (B.patdnn_variant_name(v), ksplit, "workspace", err)
+                    # a workspace that is too small is not used: the call runs as without one
+                    buf.fill_(12345.0)
+                    L.conv2d_ws(xt, bt, out, workspace=wbuf[guard:guard + need - 64], relu=True)
+                    torch.cuda.synchronize()
+                    err = float(np.abs(out.cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max())
+                    assert err <= TOL, (B.patdnn_variant_name(v), ksplit, "short workspace", err)
     finally:
         L.close()
     assert seen > 0
@@ -187,4 +213,36 @@ def test_layer_pruned_by_the_projection_operators(torch, oracle):
     err = float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
     _say(f"    projected layer: rel_err={err:.2e}; filter lengths {L.stats()['min_filter_length']}..{L.stats()['max_filter_length']}")
     assert err <= TOL
+    L.close()
+
+
+@pytest.mark.parametrize("shape", [(12, 16), (9, 11)])     # planes of whole float4s, and not
+def test_many_slices_with_a_workspace(torch, oracle, shape):
+    """Up to 16 channel slices, each storing to its own buffer: the finishing kernel adds them
+    in groups of eight, four and one (every tier of its loop), for planes it reads as float4
+    and planes it reads float by float; atomics and buffers must both match the oracle."""
+    h, w = shape
+    rng = np.random.default_rng(31 + h)
+    lib = wl.pattern_library(wl.PATTERN_SEED)
+    c_out, c_in, n = 24, 64, 2
+    ids = rng.integers(0, 8, (c_out, c_in), dtype=np.uint8)
+    mask = (rng.random((c_out, c_in)) < 0.5).astype(np.uint8)
+    wt = rng.standard_normal((c_out, c_in, 3, 3)).astype(np.float32)
+    bias = rng.standard_normal(c_out).astype(np.float32)
+    x = rng.standard_normal((n, c_in, h, w)).astype(np.float32)
+    ref = oracle.conv2d(wt, ids, mask, lib, x, bias, relu=True, skip_removed=True)
+    names = {B.patdnn_variant_name(v): v for v in range(B.patdnn_num_variants())}
+    L = B.Layer(wt, ids, mask, lib)
+    xt, bt = torch.from_numpy(x).cuda(), torch.from_numpy(bias).cuda()
+    for vname in ("t_g8_p7x2_s1_x8_thw1b", "t_g8_p7x1_s1_x16_th"):
+        for ksplit in (5, 9, 13, 16):
+            L.set_config(names[vname], 4, 4, ksplit)
+            need = L.workspace_floats(n, h, w)
+            ws = torch.full((need,), float("nan"), dtype=torch.float32, device="cuda")
+            got = L.conv2d_ws(xt, bt, workspace=ws, relu=True).cpu().numpy()
+            plain = L.conv2d(xt, bt, relu=True).cpu().numpy()
+            e1 = float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
+            e2 = float(np.abs(plain.astype(np.float64) - ref).max() / np.abs(ref).max())
+            _say(f"    {vname} {h}x{w} ksplit {ksplit}: buffers {e1:.2e} atomics {e2:.2e}")
+            assert e1 <= TOL and e2 <= TOL, (vname, ksplit, e1, e2)
     L.close()

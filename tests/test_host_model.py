@@ -72,7 +72,8 @@ def _build_hostmodel(build, edit=None):
     L = ctypes.CDLL(str(lib))
     L.hostmodel_run.restype = ctypes.c_long
     L.hostmodel_run.argtypes = [ctypes.c_int] * 5 + [ctypes.c_void_p] * 4 + [ctypes.c_int] * 10 + \
-                               [ctypes.c_void_p] * 3 + [ctypes.c_int, ctypes.c_int, ctypes.c_char_p, ctypes.c_int]
+                               [ctypes.c_void_p] * 3 + [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                                        ctypes.c_char_p, ctypes.c_int]
     return L
 
 
@@ -81,7 +82,10 @@ def hostmodel(tmp_path_factory):
     return _build_hostmodel(tmp_path_factory.mktemp("hostmodel"))
 
 
-def _run(hostmodel, v, t, x, bias, pad, stride, relu, waves, c_out, w9=None, ksplit=1):
+def _run(hostmodel, v, t, x, bias, pad, stride, relu, waves, c_out, w9=None, ksplit=1, slice_buffers=False):
+    """slice_buffers: the split launch gets room for one partial-sum buffer per channel slice
+    (it then stores instead of adding with atomics); the room is guarded on both sides and starts
+    as NaN, so a store outside it or an element that no slice wrote shows."""
     n, c_in, h, w = x.shape
     ho, wo = (h + 2 * pad - 3) // stride + 1, (w + 2 * pad - 3) // stride + 1
     guard = 1024
@@ -91,12 +95,23 @@ def _run(hostmodel, v, t, x, bias, pad, stride, relu, waves, c_out, w9=None, ksp
     msg = ctypes.create_string_buffer(512)
     x = np.ascontiguousarray(x)
     ptr = lambda a: None if a is None else a.ctypes.data
+    scratch, scratch_floats, sbuf = None, 0, None
+    if slice_buffers:
+        scratch_floats = ksplit * (-(-(n * c_out * ho * wo) // 64) * 64)
+        sbuf = np.full(scratch_floats + 2 * guard, 555.0, np.float32)
+        # 16-byte aligned start of the room, as the launcher demands
+        skip = guard + (-(sbuf.ctypes.data + 4 * guard) % 16) // 4
+        sbuf[skip:skip + scratch_floats] = np.nan
+        scratch = sbuf.ctypes.data + 4 * skip
     errs = hostmodel.hostmodel_run(v - 1, t["G"], t["num_groups"], t["ck"], t["num_chunks"],
                                    ptr(t["slot_channel"]), ptr(t.get("chunk_ptr")), ptr(t.get("steps")), ptr(w9),
                                    n, c_in, c_out, h, w, ho, wo, stride, pad, int(relu), ptr(x), ptr(bias),
-                                   out.ctypes.data, waves, ksplit, msg, 512)
+                                   out.ctypes.data, waves, ksplit, scratch, scratch_floats, msg, 512)
     assert errs == 0, msg.value.decode()
     assert (buf[:guard] == 777.0).all() and (buf[-guard:] == 777.0).all(), "write outside the output tensor"
+    if sbuf is not None:
+        assert (sbuf[:skip] == 555.0).all() and (sbuf[skip + scratch_floats:] == 555.0).all(), \
+            "write outside the partial-sum buffers"
     return out.reshape(n, c_out, ho, wo)
 
 
@@ -131,13 +146,16 @@ def test_every_sparse_variant_on_the_host_model(hostmodel, oracle, case):
             continue
         lds_per_channel = hostmodel.hostmodel_variant_lds_floats(v - 1)
         min_waves = -(-lds_per_channel // (64 * hostmodel.hostmodel_variant_max_slots(v - 1)))   # staging slots
-        for ksplit in (1, min(3, t["num_chunks"])):
+        ks = min(3, t["num_chunks"])
+        for ksplit, slice_buffers in ((1, False), (ks, False), (ks, True)):
+            if slice_buffers and ksplit == 1:
+                continue
             got = _run(hostmodel, v, t, x, bias, case["pad"], stride, True, max(case["waves"], min_waves, 3),
-                       case["c_out"], ksplit=ksplit)
+                       case["c_out"], ksplit=ksplit, slice_buffers=slice_buffers)
             assert not np.isnan(got).any(), (B.patdnn_variant_name(v), "output element never written or unstaged LDS read")
             err = float(np.abs(got.astype(np.float64) - ref).max() / np.abs(ref).max())
-            print(f"  {B.patdnn_variant_name(v)} ksplit={ksplit}: rel_err={err:.2e}")
-            assert err <= TOL, (B.patdnn_variant_name(v), ksplit, err)
+            print(f"  {B.patdnn_variant_name(v)} ksplit={ksplit} buffers={slice_buffers}: rel_err={err:.2e}")
+            assert err <= TOL, (B.patdnn_variant_name(v), ksplit, slice_buffers, err)
         seen += 1
     L.close()
     assert seen >= 2
