@@ -466,7 +466,9 @@ def main() -> int:
             for ly in one:
                 ly["L"].close()
             res["note"] = ("13 layers chained on real activations, 5 fused ReLU + 2x2 max-pool epilogues "
-                           "(18 kernel launches per image); the graph run is one hipGraphLaunch")
+                           "(a layer that splits its input channels is two launches: slices into the "
+                           "stack's partial-sum buffers, then sum + bias + ReLU / pool); the graph run is "
+                           "one hipGraphLaunch")
             return res
 
         latency = {"note": "one image, all layers launched back to back on one stream, launch gaps included"}
