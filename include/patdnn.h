@@ -161,8 +161,9 @@ patdnn_status_t patdnn_conv2d_pool(patdnn_handle_t h, const float* input, int32_
  *   pool2             non-zero: ReLU + 2x2 max pooling fused as in patdnn_conv2d_pool (`fuse_relu`
  *                     is then implied and `output` is the pooled tensor); a pooled layer
  *                     keeps its split configuration only with a workspace
- *   workspace         DEVICE, 16-byte aligned (else PATDNN_EINVAL), caller-owned, contents
- *                     undefined before and after; may be NULL (then as the plain calls)
+ *   workspace         DEVICE, 16-byte aligned and apart from input and output (else
+ *                     PATDNN_EINVAL), caller-owned, contents undefined before and after; may
+ *                     be NULL (then as the plain calls)
  *   workspace_floats  its size; if it is smaller than the layer needs the call runs as
  *                     without one
  * Calls that share a workspace must not overlap in time.  Nothing is allocated.

@@ -570,6 +570,17 @@ patdnn_status_t patdnn_conv2d_ws(patdnn_handle_t h, const float* input, int32_t 
 {
     if (workspace && (reinterpret_cast<uintptr_t>(workspace) & 15))
         return fail(PATDNN_EINVAL, "workspace must be 16-byte aligned");
+    ConvShape s{};
+    if (workspace && workspace_floats && input && output && shape_of(h, n, h_in, w_in, s) == PATDNN_OK) {
+        const char* lo = reinterpret_cast<const char*>(workspace);
+        const char* hi = lo + 4ull * workspace_floats;
+        const char* in_lo = reinterpret_cast<const char*>(input);
+        const char* in_hi = in_lo + 4ull * (size_t)n * s.c_in * s.h * s.w;
+        const char* out_lo = reinterpret_cast<const char*>(output);
+        const char* out_hi = out_lo + 4ull * (size_t)n * s.c_out * (pool2 ? s.ho / 2 : s.ho) * (pool2 ? s.wo / 2 : s.wo);
+        if ((lo < in_hi && in_lo < hi) || (lo < out_hi && out_lo < hi))
+            return fail(PATDNN_EINVAL, "workspace overlaps input or output");
+    }
     return conv2d_impl(h, input, n, h_in, w_in, bias, output, pool2 ? 1 : fuse_relu, pool2 ? 1 : 0,
                        static_cast<hipStream_t>(stream), workspace, workspace ? workspace_floats : 0);
 }

@@ -193,6 +193,14 @@ def test_degenerate_layers(torch, oracle):
     with pytest.raises(B.PatdnnError) as e:
         L.conv2d(xin, None, bad_out)
     assert e.value.status == B.PATDNN_EINVAL
+    # so is a workspace that overlaps the input or the output, or is not 16-byte aligned
+    good_out = torch.zeros((2, 20, 10, 10), device="cuda")
+    spare = torch.zeros(4096, device="cuda")
+    for ws in (both[2000:6000], good_out.view(-1)[400:2000], spare[1:1025]):
+        with pytest.raises(B.PatdnnError) as e:
+            L.conv2d_ws(xin, None, good_out, workspace=ws)
+        assert e.value.status == B.PATDNN_EINVAL
+    L.conv2d_ws(xin, None, good_out, workspace=spare)         # a fine one, unused by an unsplit layer
     L.close()
 
 
