@@ -421,7 +421,47 @@ __global__ __launch_bounds__(512) void tiled_conv_kernel(TiledArgs a)
     }
     if (!written && group_ok && band_ok) {
         const size_t oplane = (size_t)a.ho * a.wo;
-        if (!SPLITK && a.pool) {
+        if (!SPLITK && a.pool && PC == 2) {
+            // ReLU + 2x2 max pooling with two columns per lane: a lane's columns are the two
+            // columns of one pooled column (ox0 is even), and of its PR rows all but one pair up
+            // inside the patch, so most pooled cells are complete in registers and go out as
+            // plain stores; only the row whose partner belongs to the band above or below (the
+            // first row where the band starts at an odd row, else the last) is folded into its
+            // zeroed cell with the atomic max, like the values of the general path below.
+            const int pho = a.ho >> 1, pwo = a.wo >> 1;
+            const int px = ox0 >> 1;
+            const bool odd_start = (oy0 & 1) != 0;
+#pragma unroll
+            for (int s = 0; s < G; ++s) {
+                const int co = load_uniform(a.slot_channel, group * G + s);
+                if (co < 0) continue;
+                const float b = a.bias ? load_uniform(a.bias, co) : 0.0f;
+                float* dstf = a.out + ((size_t)img * a.c_out + co) * ((size_t)pho * pwo);
+                unsigned* dst = reinterpret_cast<unsigned*>(dstf);
+                float m[PR];                     // max over the lane's two columns, ReLU applied
+#pragma unroll
+                for (int r = 0; r < PR; ++r) m[r] = fmaxf(fmaxf(acc[s][r * PC], acc[s][r * PC + 1]) + b, 0.0f);
+                if (px < pwo) {
+#pragma unroll
+                    for (int r = 0; r + 1 < PR; ++r) {
+                        // rows r, r + 1 form a window if the upper one is an even row of the image
+                        const int oy = oy0 + r;
+                        if (((r & 1) != 0) == odd_start && (oy >> 1) < pho)
+                            dstf[(size_t)(oy >> 1) * pwo + px] = fmaxf(m[r], m[r + 1]);
+                    }
+                    // the row left over: 0 for a band that starts at an odd row, else the last one
+                    // if the patch has an odd number of rows
+                    if (odd_start) {
+                        if (m[0] > 0.0f && (oy0 >> 1) < pho) atomicMax(&dst[(size_t)(oy0 >> 1) * pwo + px], __float_as_uint(m[0]));
+                    }
+                    if (((PR & 1) != 0) != odd_start) {
+                        const int oy = oy0 + PR - 1;
+                        if (m[PR - 1] > 0.0f && (oy >> 1) < pho)
+                            atomicMax(&dst[(size_t)(oy >> 1) * pwo + px], __float_as_uint(m[PR - 1]));
+                    }
+                }
+            }
+        } else if (!SPLITK && a.pool) {
             // ReLU + 2x2 max pooling: fold every value into its pooled cell (zero beforehand)
             const int pho = a.ho >> 1, pwo = a.wo >> 1;
 #pragma unroll
