@@ -65,7 +65,7 @@ struct TiledArgs {
 // Phase timeline for performance work: a build with -DPATDNN_TIMELINE makes every wavefront add
 // up the cycles it spends in each phase (prologue, waiting for staged data, issuing staging
 // loads, the chunk's kernels, epilogue, barriers) and write the totals to the buffer given to
-// patdnn_debug_timeline(); the figures in the design notes come from it.  The product build
+// patdnn_debug_timeline(): a tool for finding where a wavefront's time goes.  The product build
 // does not define the macro and compiles none of it.
 #ifdef PATDNN_TIMELINE
 #define TL_DECL unsigned long long tl_t = __builtin_readcyclecounter(), tl_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}
