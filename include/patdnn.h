@@ -369,9 +369,13 @@ void        patdnn_destroy(patdnn_handle_t h);          /* NULL is a no-op */
  * A stack of layers run back to back on one stream - the paper's headline scenario, one
  * image through all CONV layers of a network (section 6.2).  Layer i reads what layer
  * i-1 wrote; `pool2` fuses ReLU + 2x2 max pooling into the layer (as patdnn_conv2d_pool).
- * The stack owns two DEVICE buffers for the tensors between layers (allocated by
- * patdnn_stack_create, freed by patdnn_stack_destroy); handles and bias arrays stay the
- * caller's and must outlive the stack.
+ * The stack owns two DEVICE buffers for the tensors between layers and one for partial sums
+ * (allocated by patdnn_stack_create, freed by patdnn_stack_destroy): layers that are
+ * configured, when the stack is created, to split their input channels get the workspace of
+ * patdnn_conv2d_ws from it (one buffer per channel slice, up to 512 MB; a layer that would
+ * need more, or is reconfigured later to need more than there is, adds its slices up with
+ * atomics as patdnn_conv2d does).  Handles and bias arrays stay the caller's and must outlive
+ * the stack.
  *   patdnn_stack_run, use_graph == 0: every launch goes to `stream` directly.
  *   use_graph != 0: the launches are recorded once into a HIP graph (stream capture on
  *   `stream`, which must not be the default stream; preceded by one plain run the first
@@ -399,14 +403,17 @@ void            patdnn_stack_destroy(patdnn_stack_t s);     /* NULL is a no-op *
  * patdnn_stack_run (use_graph == 0) for callers that must not allocate or cannot let a
  * library allocate on their behalf - code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc: the tensors between the layers and the partial sums of
- * split pooled layers live in a device array built into the library (32 MiB per GPU, held
- * until the process ends) instead of the stack's own buffers.  The call allocates and frees
- * nothing.  PATDNN_EUNSUPPORTED (with the two sizes in patdnn_last_error) if the stack needs
- * more than the array holds: the sum, each rounded up to 256 bytes, of the largest tensor
+ * split layers live in a device array built into the library (32 MiB per GPU, held until the
+ * process ends) instead of the stack's own buffers.  The call allocates and frees nothing.
+ * PATDNN_EUNSUPPORTED (with the two sizes in patdnn_last_error) if the stack needs more
+ * than the array holds: the sum, each rounded up to 256 bytes, of the largest tensor
  * written by the even-numbered layers, the largest written by the odd-numbered layers (the
- * last layer writes `output`) and the largest un-pooled output of a pooled layer.  All calls
- * on one GPU share the array: calls that overlap in time on the same GPU race.  Results are
- * those of patdnn_stack_run.
+ * last layer writes `output`) and the largest un-pooled output of a pooled layer.  If the
+ * array also has room for one partial-sum buffer per channel slice (the stack's own third
+ * buffer) the split layers use it as in patdnn_stack_run; otherwise they add their slices
+ * up with atomics.  All calls on one GPU share the array: calls that overlap in time on the
+ * same GPU race.  Results are those of patdnn_stack_run within the tolerance of a sum
+ * taken in another order.
  */
 patdnn_status_t patdnn_stack_run_static(patdnn_stack_t s, const float* input, float* output,   /* DEVICE */
                                         void* stream);
