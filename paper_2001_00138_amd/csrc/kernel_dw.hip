@@ -51,25 +51,59 @@ __device__ __forceinline__ void ld4(const __half* p, float& a, float& b, float& 
 }
 __device__ __forceinline__ void st1(float* p, float v) { *p = v; }
 __device__ __forceinline__ void st1(__half* p, float v) { *p = __float2half_rn(v); }
-__device__ __forceinline__ void st4(float* p, const float (&v)[4]) { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
-__device__ __forceinline__ void st4(__half* p, const float (&v)[4])
+// NP consecutive elements at an address aligned to NP elements: 16-byte accesses for four
+// floats or eight binary16 values
+template <int NP>
+__device__ __forceinline__ void ldv(const float* p, float* v)
 {
-    const __half2 lo = __floats2half2_rn(v[0], v[1]), hi = __floats2half2_rn(v[2], v[3]);
-    uint2 m;
-    m.x = *reinterpret_cast<const unsigned*>(&lo);
-    m.y = *reinterpret_cast<const unsigned*>(&hi);
-    *reinterpret_cast<uint2*>(p) = m;
+#pragma unroll
+    for (int k = 0; k < NP; k += 4) ld4(p + k, v[k], v[k + 1], v[k + 2], v[k + 3]);
+}
+template <int NP>
+__device__ __forceinline__ void ldv(const __half* p, float* v)
+{
+    if constexpr (NP == 8) {
+        const uint4 m = *reinterpret_cast<const uint4*>(p);
+        const unsigned w[4] = {m.x, m.y, m.z, m.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const __half2 h = *reinterpret_cast<const __half2*>(&w[k]);
+            v[2 * k] = __low2float(h);
+            v[2 * k + 1] = __high2float(h);
+        }
+    } else {
+        ld4(p, v[0], v[1], v[2], v[3]);
+    }
+}
+template <int NP>
+__device__ __forceinline__ void stv(float* p, const float (&v)[NP])
+{
+#pragma unroll
+    for (int k = 0; k < NP; k += 4) *reinterpret_cast<float4*>(p + k) = make_float4(v[k], v[k + 1], v[k + 2], v[k + 3]);
+}
+template <int NP>
+__device__ __forceinline__ void stv(__half* p, const float (&v)[NP])
+{
+    unsigned w[NP / 2];
+#pragma unroll
+    for (int k = 0; k < NP / 2; ++k) {
+        const __half2 h = __floats2half2_rn(v[2 * k], v[2 * k + 1]);
+        w[k] = *reinterpret_cast<const unsigned*>(&h);
+    }
+    if constexpr (NP == 8) *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    else *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
 }
 
-// S: stride.  VEC: rows start aligned to four elements (w % 4 == 0, aligned base) -> vector loads.
-// VST: output rows aligned to four elements (wo % 4 == 0, aligned base) -> one vector store.
-template <int S, bool VEC, bool VST, class T>
+// S: stride.  NP: outputs per lane (4; 8 on binary16 storage where the rows allow, so that a
+// lane still moves 16 bytes per access).  VEC: rows start aligned to NP elements (w % NP == 0,
+// aligned base) -> vector loads.  VST: output rows aligned to NP elements -> one vector store.
+template <int S, int NP, bool VEC, bool VST, class T>
 __global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs<T> a)
 {
-    constexpr int NC = 3 * S + 3;                  // input columns under four outputs: 6 or 9
+    constexpr int NC = (NP - 1) * S + 3;           // input columns under NP outputs
     const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
     if (t >= a.total) return;
-    // lane number -> (image n, stored channel f, output row oy, group of four columns xq).  A
+    // lane number -> (image n, stored channel f, output row oy, group of NP columns xq).  A
     // thread has a dozen FMAs to do, so three 64-bit divisions would be most of its
     // instructions and the kernel would be bound by them instead of by HBM: below 2^31 lanes
     // they are multiplications by launch-time constants.
@@ -97,10 +131,12 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs<T> a)
     float4 wv;
     ld4(a.dw_weight + (size_t)f * 4, wv.x, wv.y, wv.z, wv.w);
     const T* plane = a.in + ((size_t)n * a.c + co) * ((size_t)a.h * a.w);
-    const int ox0 = xq * 4;
+    const int ox0 = xq * NP;
     const int ix0 = ox0 * S - a.pad;               // input column under (output ox0, tap 0)
 
-    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float acc[NP];
+#pragma unroll
+    for (int i = 0; i < NP; ++i) acc[i] = 0.0f;
 #pragma unroll
     for (int dy = 0; dy < 3; ++dy) {
         const unsigned rowbits = (mask >> (3 * dy)) & 7u;
@@ -110,30 +146,34 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs<T> a)
         const T* row = plane + (size_t)iy * a.w;
         float v[NC];
         if constexpr (VEC) {
-            // pad is 0 or 1: columns ix0 + pad .. are 16-byte aligned
+            // pad is 0 or 1: columns ix0 + pad .. start a vector
             if (a.pad == 1) {
                 v[0] = ((rowbits & 1u) && ix0 >= 0) ? ld1(row + ix0) : 0.0f;
 #pragma unroll
-                for (int q = 0; q < (NC - 1) / 4; ++q) {
-                    const int ix = ix0 + 1 + 4 * q;
-                    float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (ix < a.w) ld4(row + ix, m.x, m.y, m.z, m.w);
-                    v[1 + 4 * q] = m.x; v[2 + 4 * q] = m.y; v[3 + 4 * q] = m.z; v[4 + 4 * q] = m.w;
+                for (int q = 0; q < (NC - 1) / NP; ++q) {
+                    const int ix = ix0 + 1 + NP * q;
+                    float m[NP];
+#pragma unroll
+                    for (int k = 0; k < NP; ++k) m[k] = 0.0f;
+                    if (ix < a.w) ldv<NP>(row + ix, m);
+#pragma unroll
+                    for (int k = 0; k < NP; ++k) v[1 + NP * q + k] = m[k];
                 }
                 if constexpr (S == 1) {
-                    const int ix = ix0 + 5;
-                    v[5] = ((rowbits & 4u) && ix < a.w) ? ld1(row + ix) : 0.0f;
+                    const int ix = ix0 + NP + 1;
+                    v[NP + 1] = ((rowbits & 4u) && ix < a.w) ? ld1(row + ix) : 0.0f;
                 }
             } else {
 #pragma unroll
-                for (int q = 0; q < (NC + 3) / 4; ++q) {
-                    const int ix = ix0 + 4 * q;
-                    float4 m = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (ix < a.w) ld4(row + ix, m.x, m.y, m.z, m.w);
-                    if (4 * q + 0 < NC) v[4 * q + 0] = m.x;
-                    if (4 * q + 1 < NC) v[4 * q + 1] = m.y;
-                    if (4 * q + 2 < NC) v[4 * q + 2] = m.z;
-                    if (4 * q + 3 < NC) v[4 * q + 3] = m.w;
+                for (int q = 0; q < (NC + NP - 1) / NP; ++q) {
+                    const int ix = ix0 + NP * q;
+                    float m[NP];
+#pragma unroll
+                    for (int k = 0; k < NP; ++k) m[k] = 0.0f;
+                    if (ix < a.w) ldv<NP>(row + ix, m);
+#pragma unroll
+                    for (int k = 0; k < NP; ++k)
+                        if (NP * q + k < NC) v[NP * q + k] = m[k];
                 }
             }
         } else {
@@ -150,21 +190,21 @@ __global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs<T> a)
             const int rank = __builtin_popcount(mask & ((1u << (3 * dy + dx)) - 1u));
             const float wt = rank == 0 ? wv.x : rank == 1 ? wv.y : rank == 2 ? wv.z : wv.w;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) acc[i] = fmaf(wt, v[i * S + dx], acc[i]);
+            for (int i = 0; i < NP; ++i) acc[i] = fmaf(wt, v[i * S + dx], acc[i]);
         }
     }
     const float b = a.bias ? a.bias[co] : 0.0f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NP; ++i) {
         acc[i] += b;
         if (a.relu) acc[i] = fmaxf(acc[i], 0.0f);
     }
     T* dst = a.out + (((size_t)n * a.c + co) * a.ho + oy) * (size_t)a.wo + ox0;
     if constexpr (VST) {
-        st4(dst, acc);
+        stv<NP>(dst, acc);
     } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < NP; ++i)
             if (ox0 + i < a.wo) st1(dst + i, acc[i]);
     }
 }
@@ -177,7 +217,13 @@ static hipError_t launch_dw_t(const DevFkw& f, const T* weights, const ConvShape
     a.reorder = f.reorder; a.dw_mask = f.dw_mask; a.dw_weight = weights;
     a.in = in; a.bias = bias; a.out = out;
     a.c = s.c_out; a.h = s.h; a.w = s.w; a.ho = s.ho; a.wo = s.wo;
-    a.wq = (s.wo + 3) / 4; a.pad = s.pad; a.relu = s.relu;
+    // eight outputs per lane on two-byte elements where every row, in and out, is whole
+    // 16-byte vectors; four otherwise
+    constexpr uintptr_t kAlign8 = 8 * sizeof(T) - 1;
+    const bool wide = sizeof(T) == 2 && s.w % 8 == 0 && s.wo % 8 == 0 &&
+                      ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & kAlign8) == 0;
+    const int np = wide ? 8 : 4;
+    a.wq = (s.wo + np - 1) / np; a.pad = s.pad; a.relu = s.relu;
     a.total = (long long)s.n * s.c_out * s.ho * a.wq;
     a.div_wq = make_fast_div((uint32_t)a.wq);
     a.div_ho = make_fast_div((uint32_t)a.ho);
@@ -190,8 +236,13 @@ static hipError_t launch_dw_t(const DevFkw& f, const T* weights, const ConvShape
     const bool vec = s.w % 4 == 0 && (reinterpret_cast<uintptr_t>(in) & kAlign) == 0;
     const bool vst = s.wo % 4 == 0 && (reinterpret_cast<uintptr_t>(out) & kAlign) == 0;
     const dim3 grid((unsigned)blocks), block(256);
-#define PATDNN_DW_LAUNCH(S, V, W) hipLaunchKernelGGL((dw_conv_kernel<S, V, W, T>), grid, block, 0, stream, a)
-    if (s.stride == 1) {
+#define PATDNN_DW_LAUNCH(S, V, W) hipLaunchKernelGGL((dw_conv_kernel<S, 4, V, W, T>), grid, block, 0, stream, a)
+    if (wide) {
+        if constexpr (sizeof(T) == 2) {
+            if (s.stride == 1) hipLaunchKernelGGL((dw_conv_kernel<1, 8, true, true, T>), grid, block, 0, stream, a);
+            else hipLaunchKernelGGL((dw_conv_kernel<2, 8, true, true, T>), grid, block, 0, stream, a);
+        }
+    } else if (s.stride == 1) {
         if (vec && vst) PATDNN_DW_LAUNCH(1, true, true);
         else if (vec) PATDNN_DW_LAUNCH(1, true, false);
         else if (vst) PATDNN_DW_LAUNCH(1, false, true);

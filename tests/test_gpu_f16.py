@@ -76,6 +76,8 @@ def _rand(rng, c_out, c_in, keep, **kw):
     dict(c_out=37, c_in=37, n=2, h=12, w=16, keep=0.7, depthwise=True, stride=2),
     dict(c_out=21, c_in=21, n=3, h=9, w=20, keep=1.0, depthwise=True, pad=0),
     dict(c_out=64, c_in=64, n=2, h=7, w=7, keep=1.0, depthwise=True),
+    dict(c_out=29, c_in=29, n=2, h=9, w=32, keep=0.8, depthwise=True),               # eight outputs per lane
+    dict(c_out=29, c_in=29, n=2, h=11, w=48, keep=1.0, depthwise=True, stride=2),    # ... stride 2
     dict(c_out=33, c_in=33, n=2, h=30, w=130, keep=1.0, depthwise=True, stride=2),
     dict(c_out=19, c_in=19, n=3, h=17, w=9, keep=1.0, depthwise=True, stride=2),
     dict(c_out=24, c_in=20, n=3, h=13, w=13, keep=0.3),
