@@ -405,6 +405,28 @@ def test_an_explicit_configuration_is_strict():
     L.close()
 
 
+def test_workspace_size_follows_the_configuration():
+    """patdnn_workspace_floats: one buffer of the un-pooled output, rounded up to 64 floats, per
+    channel slice of the present configuration; nothing for a configuration that does not split,
+    for the default configuration, or for arguments the convolution would reject."""
+    rng = np.random.default_rng(4)
+    lib = wl.pattern_library(wl.PATTERN_SEED)
+    c_out, c_in = 24, 40
+    L = B.Layer(rng.standard_normal((c_out, c_in, 3, 3)).astype(np.float32),
+                rng.integers(0, 8, (c_out, c_in), dtype=np.uint8),
+                (rng.random((c_out, c_in)) < 0.5).astype(np.uint8), lib, pad=0, host_only=True)
+    assert L.workspace_floats(2, 13, 17) == 0                      # default configuration
+    for ksplit in (1, 2, 5):
+        L.set_config(1, 8, 4, ksplit)
+        for n, h, w in ((2, 13, 17), (1, 8, 8), (3, 30, 5)):
+            full = n * c_out * (h - 2) * (w - 2)
+            want = 0 if ksplit == 1 else ksplit * (-(-full // 64) * 64)
+            assert L.workspace_floats(n, h, w) == want, (ksplit, n, h, w)
+    assert L.workspace_floats(1, 2, 9) == 0                        # smaller than the kernel: rejected
+    assert L.workspace_floats(1, 0, 9) == 0
+    L.close()
+
+
 @pytest.mark.parametrize("config,layer", [(1, 0), (2, 3), (3, 3)])
 def test_exported_csr_is_the_textbook_csr_of_the_pruned_layer(config, layer):
     """The CSR arrays the comparison kernel reads, against the oracle's CSR (itself pinned to
