@@ -152,28 +152,38 @@ def test_vgg_stack_matches_the_oracle_chain(torch, oracle, depth, tuned):
     (1, 2, 1, 2, 2, 1, 2),        # unsplit layers have no finishing kernel: the next one fills for itself
     (2, 1, 2, 1, 1, 2, 1),        # ... and unsplit pooled layers after split ones get their output zeroed
 ])
-def test_neighbouring_layers_share_zero_fills(torch, oracle, ksplits):
-    """Inside a stack a layer whose input channels are split clears, in its finishing kernel,
-    what the next layer accumulates into (its output, its pooled output or the partial-sum
-    buffer).  Every pairing of split / unsplit and pooled / plain neighbours must still match the
-    oracle's chain, also on later runs, when the buffers between the layers hold old values."""
+@pytest.mark.parametrize("configured", ["before", "after"])
+def test_neighbouring_layers_share_zero_fills(torch, oracle, ksplits, configured):
+    """Every pairing of split / unsplit and pooled / plain neighbours in a stack must match the
+    oracle's chain, also on later runs, when the buffers between the layers hold old values.
+    Configured before the stack is created, the split layers find one partial-sum buffer per
+    slice in it and store; configured afterwards they find room for one buffer at most and add
+    their slices up with atomics - then a split layer clears, in its finishing kernel, what
+    the next layer accumulates into (its output, its pooled output or the partial-sum buffer)."""
     from oracle import stack as ostack
     layers, pool = _vgg_prefix(len(ksplits))
     x = layers[0]["input"]
     ref = ostack.stack_forward(layers, x, pool)
     names = {B.patdnn_variant_name(v): v for v in range(B.patdnn_num_variants())}
     Ls = [B.Layer.from_workload(d) for d in layers]
-    for L, d, k in zip(Ls, layers, ksplits):
-        if d["spec"].c_in >= 16:                 # the first layer (3 channels) has a single chunk to split
-            L.set_config(names["t_g8_p7x2_s1_x8_thw1b"], 8, 4, k)
     biases = [torch.from_numpy(d["bias"]).cuda() for d in layers]
+
+    def configure():
+        for L, d, k in zip(Ls, layers, ksplits):
+            if d["spec"].c_in >= 16:             # the first layer (3 channels) has a single chunk to split
+                L.set_config(names["t_g8_p7x2_s1_x8_thw1b"], 8, 4, k)
+
+    if configured == "before":
+        configure()
     st = B.Stack([(L, b, True, p) for L, b, p in zip(Ls, biases, pool)], 1, x.shape[2], x.shape[3])
+    if configured == "after":
+        configure()
     xt = torch.from_numpy(x).cuda()
     for rep in range(3):
         out = st.run(xt)
         torch.cuda.synchronize()
         err = _rel(out.cpu().numpy(), ref[-1])
-        _say(f"    ksplits {ksplits} run {rep}: rel_err={err:.2e}")
+        _say(f"    ksplits {ksplits} configured {configured} run {rep}: rel_err={err:.2e}")
         assert err <= TOL
     st.close()
     for L in Ls:
